@@ -1,0 +1,343 @@
+"""CPU-only pins of the fp64 oracle against things other than itself: library routines, closed
+forms, invariants and brute force on tiny inputs.  A plausible mistake in the oracle (dropped
+term, wrong sign or index, transposed operand, wrong centroid version) fails at least one."""
+import math
+
+import numpy as np
+import pytest
+import torch
+from scipy.spatial.distance import cdist
+from sklearn.cluster import KMeans
+
+from oracle import svoo_oracle as so
+from paper_2603_18636_amd import synth
+
+CFG0 = synth.CONFIGS[0]
+
+
+def tiny_head(seed_layer=0, grid=(2, 8, 8), d=16, n_seeds=6, kq=4, kk=5):
+    return synth.make_head(CFG0, seed_layer, 0, grid=grid, d=d, n_seeds=n_seeds, kq=kq, kk=kk)
+
+
+# ---------------------------------------------------------------------------- attention
+def test_dense_attention_matches_library_sdpa():
+    """softmax(q K^T / sqrt(d)) V (Sec. 4.1, definition of z_i) against torch's fp64 SDPA."""
+    h = synth.make_head(CFG0, 0, 0)
+    q, k, v = (torch.from_numpy(h[x].astype(np.float64)) for x in "qkv")
+    ref = torch.nn.functional.scaled_dot_product_attention(q[None], k[None], v[None])[0].numpy()
+    got = so.dense_attention(h["q"], h["k"], h["v"], 1.0 / math.sqrt(64))
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    rows = np.array([3, 77, 1023])
+    np.testing.assert_allclose(so.dense_attention(h["q"], h["k"], h["v"], 0.125, rows=rows), ref[rows], atol=1e-12)
+
+
+@pytest.mark.parametrize("label_kind", ["clustered", "random", "with_empty"])
+def test_keep_everything_equals_dense(label_kind):
+    """keep = 1 and tau = 1 keeps every non-empty block, so the sparse path must reproduce dense
+    attention for ANY labels (pins selection clamps, empty-cluster handling and the masked softmax)."""
+    h = synth.make_head(CFG0, 1, 0)
+    n, kq, kk = 1024, 16, 16
+    rng = np.random.default_rng(5)
+    if label_kind == "clustered":
+        cc = so.cocluster(h["q"], h["k"], h["init_q_idx"], h["init_k_idx"], 2)
+        lq, lk, cq, ck = cc["labels_q"], cc["labels_k"], cc["cq"], cc["ck"]
+    else:
+        lq = rng.integers(0, kq, n).astype(np.int32)
+        lk = rng.integers(0, kk, n).astype(np.int32)
+        if label_kind == "with_empty":
+            lq[lq == 3] = 4
+            lk[lk == 0] = 9
+            lk[lk == 15] = 9
+        cq = rng.standard_normal((kq, 64))
+        ck = rng.standard_normal((kk, 64))
+    nq = np.bincount(lq, minlength=kq)
+    nk = np.bincount(lk, minlength=kk)
+    mask = so.block_mask(cq, ck, nq, nk, keep=1.0, tau=1.0, theta=0.1, scale=0.125)
+    assert (mask == ((nq[:, None] > 0) & (nk[None, :] > 0))).all()
+    got = so.sparse_attention(h["q"], h["k"], h["v"], lq, lk, mask, 0.125)
+    ref = so.dense_attention(h["q"], h["k"], h["v"], 0.125)
+    np.testing.assert_allclose(got, ref, atol=1e-12)
+    assert abs(so.kept_fraction(mask, nq, nk) - 1.0) < 1e-15
+
+
+def test_sparse_attention_matches_explicit_masked_matrix():
+    """Tiny case: form the full N x N score matrix, set dropped entries to -inf, softmax with a
+    library routine, multiply.  Pins which (query, key) pairs the block mask lets through."""
+    h = tiny_head()
+    n = h["q"].shape[0]
+    rng = np.random.default_rng(1)
+    lq = rng.integers(0, 4, n)
+    lk = rng.integers(0, 5, n)
+    mask = rng.random((4, 5)) < 0.5
+    mask[np.arange(4), rng.integers(0, 5, 4)] = True
+    s = torch.from_numpy(h["q"].astype(np.float64) @ h["k"].astype(np.float64).T * 0.25)
+    allowed = torch.from_numpy(mask[lq][:, lk])
+    p = torch.softmax(s.masked_fill(~allowed, float("-inf")), dim=1)
+    ref = (p @ torch.from_numpy(h["v"].astype(np.float64))).numpy()
+    got = so.sparse_attention(h["q"], h["k"], h["v"], lq, lk, mask, 0.25)
+    np.testing.assert_allclose(got, ref, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------- generator scale
+def test_logit_variance_closed_form():
+    """Average row-variance of the logits from the trace identity of the appendix equals the brute
+    force value, and the generator normalises it to 9 ("std about 3") before rounding."""
+    h = synth.make_head(CFG0, 0, 0)
+    q, k = h["q"].astype(np.float64), h["k"].astype(np.float64)
+    brute = (q @ k.T / math.sqrt(64)).var(axis=1).mean()
+    closed = synth.logit_row_variance(q, k)
+    assert abs(brute - closed) < 1e-9 * brute
+    assert abs(closed - 9.0) < 1e-4
+
+
+# ---------------------------------------------------------------------------- co-clustering
+def test_step_reduces_to_lloyd_kmeans_against_sklearn():
+    """With Norm switched off and the opposite centroids equal to the identity, the affinity of a
+    token is the token itself, so one half-step is one Lloyd iteration: compare against
+    scikit-learn's KMeans started from the same centres."""
+    rng = np.random.default_rng(0)
+    d, k, n = 8, 5, 400
+    centres = rng.standard_normal((k, d)) * 3
+    x = centres[rng.integers(0, k, n)] + rng.standard_normal((n, d))
+    c0 = x[rng.choice(n, k, replace=False)]
+    eye = np.eye(d)
+    labels1, c1, counts1, j1, _, _ = so.half_step(x, c0, eye, norm="none")
+    km = KMeans(n_clusters=k, init=c0, n_init=1, max_iter=1, tol=0.0, algorithm="lloyd").fit(x)
+    np.testing.assert_allclose(km.cluster_centers_, c1, atol=1e-10)
+    labels2, c2, _, j2, _, _ = so.half_step(x, c1, eye, norm="none")
+    assert (km.labels_ == labels2).all()
+    assert counts1.sum() == n
+    # textbook nearest-centre assignment
+    assert (np.argmin(cdist(x, c0), axis=1) == labels1).all()
+    # Lloyd's objective is non-increasing across iterations in this mode
+    js = [j1, j2]
+    c = c2
+    for _ in range(6):
+        _, c, _, j, _, _ = so.half_step(x, c, eye, norm="none")
+        js.append(j)
+    assert all(b <= a + 1e-9 for a, b in zip(js, js[1:]))
+
+
+def test_l2_norm_assignment_is_cosine_nearest():
+    """With row-wise L2 Norm, ||p^ - pbar^_j||^2 = 2 - 2 cos(p, pbar_j): labels must equal the
+    argmin of SciPy's cosine distance between the raw affinity rows, and must not change when any
+    token or any own-side centroid is multiplied by a positive number."""
+    h = tiny_head(grid=(2, 10, 10), kq=6, kk=7)
+    k = h["k"].astype(np.float64)
+    q = h["q"].astype(np.float64)
+    cq = q[h["init_q_idx"]]
+    ck = k[h["init_k_idx"]]
+    labels, _, _, _, best, second = so.half_step(k, ck, cq, "l2")
+    cosd = cdist(k @ cq.T, ck @ cq.T, metric="cosine")
+    assert (np.argmin(cosd, axis=1) == labels).all()
+    np.testing.assert_allclose(best, 2 * cosd[np.arange(k.shape[0]), labels], atol=1e-12)
+    rng = np.random.default_rng(3)
+    k_scaled = k * rng.uniform(0.1, 10, size=(k.shape[0], 1))
+    ck_scaled = ck * rng.uniform(0.1, 10, size=(ck.shape[0], 1))
+    assert (so.half_step(k_scaled, ck, cq, "l2")[0] == labels).all()
+    assert (so.half_step(k, ck_scaled, cq, "l2")[0] == labels).all()
+    assert (second >= best).all()
+
+
+def test_centroid_versions_in_step_b():
+    """Algorithm 1: Step B compares against the NEW key centroids and the OLD query centroids."""
+    h = tiny_head(grid=(2, 10, 10), kq=6, kk=7)
+    q, k = h["q"].astype(np.float64), h["k"].astype(np.float64)
+    cq0, ck0 = q[h["init_q_idx"]], k[h["init_k_idx"]]
+    cc = so.cocluster(q, k, h["init_q_idx"], h["init_k_idx"], 1)
+    lk = so.argmin_lowest(so.affinity_distances(k, ck0, cq0, "l2"))
+    assert (lk == cc["labels_k"]).all()
+    ck1 = np.stack([k[lk == j].mean(axis=0) if (lk == j).any() else ck0[j] for j in range(7)])
+    np.testing.assert_allclose(ck1, cc["ck"], atol=1e-13)
+    lq = so.argmin_lowest(so.affinity_distances(q, cq0, ck1, "l2"))
+    assert (lq == cc["labels_q"]).all()
+    lq_wrong = so.argmin_lowest(so.affinity_distances(q, cq0, ck0, "l2"))
+    assert (lq_wrong != lq).any(), "test data cannot tell the centroid versions apart"
+
+
+def test_argmin_property_and_centroid_sums():
+    """Every half-step: the new labels' cost in the anchor space that produced them is not above
+    the previous labels' cost in that same space; counts sum to N; sum_j n_j C_j = sum_i x_i."""
+    cfg = CFG0
+    h = synth.make_head(cfg, 2, 0)
+    q, k = h["q"].astype(np.float64), h["k"].astype(np.float64)
+    cc = so.cocluster(q, k, h["init_q_idx"], h["init_k_idx"], cfg.iters)
+    prev = {"q": None, "k": None}
+    for tr in cc["trace"]:
+        x = k if tr["side"] == "k" else q
+        dist = so.affinity_distances(x, tr["c_own_in"], tr["c_opp_in"], "l2")
+        new_cost = dist[np.arange(x.shape[0]), tr["labels"]].sum()
+        assert abs(new_cost - tr["J"]) < 1e-9
+        assert (dist.min(axis=1) == dist[np.arange(x.shape[0]), tr["labels"]]).all()
+        if prev[tr["side"]] is not None:
+            old_cost = dist[np.arange(x.shape[0]), prev[tr["side"]]].sum()
+            assert new_cost <= old_cost + 1e-9
+        prev[tr["side"]] = tr["labels"]
+        counts = tr["counts"]
+        assert counts.sum() == x.shape[0]
+        live = counts > 0
+        np.testing.assert_allclose((counts[live, None] * tr["c_out"][live]).sum(axis=0), x.sum(axis=0), atol=1e-9)
+    assert (np.bincount(cc["labels_q"], minlength=16) == cc["counts_q"]).all()
+
+
+def test_mean_step_lowers_cost_without_norm():
+    """Norm off: the affinity map is linear, so replacing centroids by member means cannot raise the
+    sum of squared distances of the labels just made."""
+    h = tiny_head(grid=(2, 10, 10), kq=6, kk=7)
+    q, k = h["q"].astype(np.float64), h["k"].astype(np.float64)
+    cq, ck = q[h["init_q_idx"]], k[h["init_k_idx"]]
+    labels, ck_new, _, j_assign, _, _ = so.half_step(k, ck, cq, "none")
+    dist_after = so.affinity_distances(k, ck_new, cq, "none")
+    assert dist_after[np.arange(k.shape[0]), labels].sum() <= j_assign + 1e-9
+
+
+def test_empty_cluster_keeps_previous_centroid():
+    x = np.array([[1.0, 0.0], [1.1, 0.0], [0.9, 0.1]])
+    c_prev = np.array([[1.0, 0.0], [-5.0, -5.0]])
+    labels, c_new, counts, _, _, _ = so.half_step(x, c_prev, np.eye(2), "none")
+    assert (labels == 0).all() and counts.tolist() == [3, 0]
+    np.testing.assert_allclose(c_new[1], c_prev[1])
+    np.testing.assert_allclose(c_new[0], x.mean(axis=0))
+
+
+def test_argmin_ties_take_lowest_index():
+    x = np.array([[1.0, 0.0]])
+    c = np.array([[0.0, 1.0], [2.0, 0.0], [3.0, 0.0]])  # rows 1 and 2 are the same direction
+    labels = so.half_step(x, c, np.eye(2), "l2")[0]
+    assert labels.tolist() == [1]
+
+
+def test_permutation_invariance():
+    """Re-ordering the tokens (queries by one permutation, keys and values jointly by another) and
+    mapping the anchor indices accordingly permutes labels and outputs and leaves the mask alone."""
+    cfg = CFG0
+    h = synth.make_head(cfg, 3, 0)
+    n = h["q"].shape[0]
+    rng = np.random.default_rng(11)
+    pq, pk = rng.permutation(n), rng.permutation(n)
+    inv_q, inv_k = np.argsort(pq), np.argsort(pk)
+    base = so.layer(h["q"], h["k"], h["v"], h["init_q_idx"], h["init_k_idx"], 3, 0.3, 0.9, 0.1)
+    perm = so.layer(h["q"][pq], h["k"][pk], h["v"][pk], inv_q[h["init_q_idx"]], inv_k[h["init_k_idx"]],
+                    3, 0.3, 0.9, 0.1)
+    assert (perm["labels_q"] == base["labels_q"][pq]).all()
+    assert (perm["labels_k"] == base["labels_k"][pk]).all()
+    assert (perm["mask"] == base["mask"]).all()
+    np.testing.assert_allclose(perm["out"], base["out"][pq], atol=1e-11)
+
+
+# ---------------------------------------------------------------------------- block selection
+def zero_variance_problem(seed, n=60, d=8, kq=3, kk=4, spread=2.0):
+    rng = np.random.default_rng(seed)
+    proto_q = rng.standard_normal((kq, d)) * spread
+    proto_k = rng.standard_normal((kk, d)) * spread
+    lq = np.concatenate([np.arange(kq), rng.integers(0, kq, n - kq)])
+    lk = np.concatenate([np.arange(kk), rng.integers(0, kk, n - kk)])
+    return proto_q, proto_k, lq, lk
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("mode", ["top_p", "budget"])
+def test_selection_equals_bruteforce_block_mass(seed, mode):
+    """When every token equals its cluster prototype the size-weighted centroid softmax IS the
+    exact attention mass of each block, so selection must equal a brute-force top-p / top-k over
+    block sums of the exact N x N softmax matrix."""
+    proto_q, proto_k, lq, lk = zero_variance_problem(seed)
+    kq, kk = proto_q.shape[0], proto_k.shape[0]
+    q, k = proto_q[lq], proto_k[lk]
+    scale = 1.0 / math.sqrt(q.shape[1])
+    a = torch.softmax(torch.from_numpy(q @ k.T * scale), dim=1).numpy()
+    nq, nk = np.bincount(lq, minlength=kq), np.bincount(lk, minlength=kk)
+    tau, keep, theta = (0.8, 1.0, 0.1) if mode == "top_p" else (1.0, 0.5, 0.0)
+    got = so.block_mask(proto_q, proto_k, nq, nk, keep, tau, theta, scale)
+    for r in range(kq):
+        row = int(np.nonzero(lq == r)[0][0])
+        mass = np.array([a[row, lk == j].sum() for j in range(kk)])
+        np.testing.assert_allclose(mass, so.block_weights(proto_q, proto_k, nk, scale)[r], atol=1e-12)
+        order = sorted(range(kk), key=lambda j: (-mass[j], j))
+        if mode == "top_p":
+            n_keep, acc = 0, 0.0
+            for j in order:
+                acc += mass[j]
+                n_keep += 1
+                if acc >= tau:
+                    break
+        else:
+            n_keep = math.ceil(keep * kk)
+        expect = np.zeros(kk, dtype=bool)
+        expect[order[:n_keep]] = True
+        assert (got[r] == expect).all()
+    # small intra-cluster noise must not change the selection while block-mass gaps dominate it
+    rng = np.random.default_rng(seed + 100)
+    qn = q + 1e-9 * rng.standard_normal(q.shape)
+    kn = k + 1e-9 * rng.standard_normal(k.shape)
+    cqn = np.stack([qn[lq == r].mean(axis=0) for r in range(kq)])
+    ckn = np.stack([kn[lk == j].mean(axis=0) for j in range(kk)])
+    margins = so.selection_margins(proto_q, proto_k, nq, nk, keep, tau, theta, scale)
+    if margins.min() > 1e-6:
+        assert (so.block_mask(cqn, ckn, nq, nk, keep, tau, theta, scale) == got).all()
+
+
+def test_selection_rule_hand_cases():
+    """Hand-computed rows for the threshold-dependent rule of the selection paragraph."""
+    live = np.ones(4, dtype=bool)
+    w = np.array([0.5, 0.25, 0.125, 0.125])  # exactly representable, cumsum 0.5 0.75 0.875 1.0
+    # tau reached exactly at a prefix boundary keeps that prefix (>=)
+    assert so.select_blocks(w, live, keep=1.0, tau=0.75, theta=0.1).tolist() == [True, True, False, False]
+    assert so.select_blocks(w, live, keep=1.0, tau=0.76, theta=0.1).tolist() == [True, True, True, False]
+    # equal weights: lower index first
+    assert so.select_blocks(w, live, keep=1.0, tau=0.8, theta=0.1).tolist() == [True, True, True, False]
+    # budget above theta: the smaller of recall count (3) and ceil(0.3*4)=2
+    assert so.select_blocks(w, live, keep=0.3, tau=0.8, theta=0.1).sum() == 2
+    # budget above theta, recall count (1) smaller than budget ceil(0.9*4)=4
+    assert so.select_blocks(w, live, keep=0.9, tau=0.4, theta=0.1).tolist() == [True, False, False, False]
+    # budget at or below theta: the larger of recall count (3) and ceil(0.1*4)=1
+    assert so.select_blocks(w, live, keep=0.1, tau=0.8, theta=0.1).sum() == 3
+    assert so.select_blocks(w, live, keep=0.1, tau=0.3, theta=0.1).sum() == 1
+    # ceil: 0.26*4 = 1.04 -> 2 blocks in budget-only mode (tau=1, theta=0)
+    assert so.select_blocks(w, live, keep=0.26, tau=1.0, theta=0.0).tolist() == [True, True, False, False]
+    assert so.select_blocks(w, live, keep=0.25, tau=1.0, theta=0.0).tolist() == [True, False, False, False]
+    # empty key clusters are never selected and do not count
+    live2 = np.array([True, False, True, True])
+    w2 = np.array([0.5, 0.0, 0.25, 0.25])
+    assert so.select_blocks(w2, live2, keep=1.0, tau=1.0, theta=0.1).tolist() == [True, False, True, True]
+    assert so.select_blocks(w2, live2, keep=1.0, tau=0.6, theta=0.1).tolist() == [True, False, True, False]
+    # at least one block even if the budget rounds to zero
+    assert so.select_blocks(w, live, keep=0.0, tau=1.0, theta=-1.0).sum() == 1
+    # unsorted input: descending order is by weight, not by index
+    w3 = np.array([0.125, 0.5, 0.125, 0.25])
+    assert so.select_blocks(w3, live, keep=1.0, tau=0.75, theta=0.1).tolist() == [False, True, False, True]
+
+
+def test_block_mask_skips_empty_query_clusters():
+    cq = np.random.default_rng(0).standard_normal((3, 4))
+    ck = np.random.default_rng(1).standard_normal((2, 4))
+    m = so.block_mask(cq, ck, np.array([5, 0, 2]), np.array([3, 4]), 1.0, 1.0, 0.1, 0.5)
+    assert m.tolist() == [[True, True], [False, False], [True, True]]
+
+
+def test_block_weights_is_size_weighted_softmax():
+    cq = np.array([[1.0, 0.0]])
+    ck = np.array([[2.0, 0.0], [0.0, 0.0], [1.0, 0.0]])
+    w = so.block_weights(cq, ck, np.array([1, 3, 0]), scale=1.0)
+    e = np.array([1 * math.exp(2.0), 3 * math.exp(0.0), 0.0])
+    np.testing.assert_allclose(w[0], e / e.sum(), atol=1e-15)
+
+
+# ---------------------------------------------------------------------------- boundary helpers
+def test_stable_permutation():
+    labels = np.array([2, 0, 2, 1, 0, 2, 3])
+    perm, offsets = so.stable_permutation(labels, 5)
+    assert perm.tolist() == [1, 4, 3, 0, 2, 5, 6]
+    assert offsets.tolist() == [0, 2, 3, 6, 7, 7]
+
+
+def test_generator_is_deterministic_and_dtype_exact():
+    a = synth.make_head(synth.CONFIGS[1], 0, 3, grid=(3, 6, 8), n_seeds=8, kq=8, kk=8)
+    b = synth.make_head(synth.CONFIGS[1], 0, 3, grid=(3, 6, 8), n_seeds=8, kq=8, kk=8)
+    c = synth.make_head(synth.CONFIGS[1], 0, 4, grid=(3, 6, 8), n_seeds=8, kq=8, kk=8)
+    assert all((a[x] == b[x]).all() for x in a)
+    assert not (a["q"] == c["q"]).all()
+    synth.bf16_bits(a["q"])  # asserts representability
+    assert len(set(a["init_q_idx"].tolist())) == 8
+    x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -1.00390625], dtype=np.float32)
+    assert synth.round_to_bf16(x).tolist() == [1.0, 1.015625, -1.0]

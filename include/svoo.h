@@ -1,0 +1,173 @@
+/*
+ * svoo.h -- C boundary of the MI355X (gfx950) implementation of the ONLINE stage of SVOO:
+ * per-head block-sparse self-attention of a video Diffusion Transformer layer
+ * (paper Sec. 4.2 "Online Bidirectional Co-Clustering", Algorithm 1, paragraph
+ * "Top Block-Pair Selection"; attention itself as defined in Sec. 4.1).
+ *
+ * One layer is five calls on one HIP stream:
+ *
+ *   svoo_cocluster          Q,K            -> labels, centroids, cluster sizes        (Algorithm 1)
+ *   svoo_permute            labels, X      -> perm, offsets, X in cluster order       (implied layout)
+ *   svoo_block_mask         centroids      -> kept key blocks per query block         (Top Block-Pair Selection)
+ *   svoo_block_sparse_attn  sorted Q,K,V   -> sorted O over kept blocks only          (same paragraph, last sentence)
+ *   svoo_unpermute          sorted O, perm -> O in token order
+ *
+ * plus svoo_attn, the dense softmax(Q K^T / sqrt(d)) V used for warm-up layers/steps
+ * (Sec. 5.1 "Implementations") and as the speed-up denominator.
+ *
+ * Conventions that hold for every entry point
+ * -------------------------------------------
+ *  - Every pointer except `const svoo_shape*` is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or keeps a pointer after the call returns.  Scratch memory comes from
+ *    the caller through (ws, ws_bytes); svoo_workspace_bytes() gives a size sufficient for every
+ *    call with that shape.  `ws` must be 256-byte aligned; tensors must be 16-byte aligned.
+ *  - Tensors are dense row-major.  Q, K, V, O are [bh, n, d]: batch and heads are folded into `bh`
+ *    and every slice is an independent problem (the paper clusters per layer and per head).
+ *    dtype SVOO_BF16 = 16-bit brain float bit patterns, SVOO_F32 = IEEE binary32.
+ *  - Calls only enqueue work on `hip_stream` (a hipStream_t cast to void*; NULL = the null stream)
+ *    and return without synchronising.  Two calls that share a workspace must be ordered on one
+ *    stream.
+ *  - Return value: SVOO_OK, or an error code.  Argument errors are detected on the host before
+ *    anything is launched and leave all outputs untouched.  Nothing is printed, nothing aborts.
+ *  - Limits: d in {64, 128}; 1 <= kq, kk <= 1024; kq, kk <= n; n <= 2^24; bh >= 1.
+ *  - Cluster labels are int32 in [0, K).  An EMPTY cluster is legal everywhere: it owns zero rows
+ *    after the permute (offsets[j] == offsets[j+1]), keeps its previous centroid in
+ *    svoo_cocluster, and is never selected by svoo_block_mask.
+ *  - Outputs are fully overwritten.  Results are deterministic: the same inputs give the same
+ *    bits on every run (no floating-point atomics anywhere).
+ */
+#ifndef SVOO_H
+#define SVOO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SVOO_OK = 0,
+    SVOO_ERR_INVALID_ARG = 1,         /* null required pointer, size out of range, bad alignment */
+    SVOO_ERR_UNSUPPORTED = 2,         /* d or dtype the kernels do not cover */
+    SVOO_ERR_WORKSPACE_TOO_SMALL = 3, /* ws_bytes below what this call needs */
+    SVOO_ERR_HIP = 4                  /* a HIP launch reported an error */
+} svoo_status;
+
+typedef enum { SVOO_BF16 = 0, SVOO_F32 = 1 } svoo_dtype;
+
+typedef struct {
+    int32_t bh;     /* batch * heads: number of independent slices            */
+    int32_t n;      /* tokens per slice (flattened t*h*w latent grid)          */
+    int32_t d;      /* head dimension d' of Sec. 4.1: 64 or 128                */
+    int32_t dtype;  /* svoo_dtype of Q, K, V, O                                */
+    int32_t kq;     /* number of query blocks K_q (Algorithm 1 input)          */
+    int32_t kk;     /* number of key blocks K_k                                */
+} svoo_shape;
+
+/* Static string for a status code. */
+const char* svoo_status_string(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t svoo_version(void);
+
+/* Bytes of workspace sufficient for any call below with this shape (0 if the shape is invalid). */
+size_t svoo_workspace_bytes(const svoo_shape* shape);
+
+/*
+ * Algorithm 1, bidirectional co-clustering.  For it = 1..iters:
+ *   Step A  P = K C_q^T, Pbar = C_k C_q^T, both row-normalised (L2, floor 1e-12);
+ *           labels_k[i] = argmin_j ||P^_i - Pbar^_j||_2 (lowest j on ties); C_k[j] = mean of its keys.
+ *   Step B  the same for queries against the NEW C_k, with the OLD C_q as own-side centroids.
+ * Sample(.) of the algorithm's first line is an input: initial centroids are the rows
+ * q[init_q_idx[c]] / k[init_k_idx[c]] (indices in [0, n)), or, when init_cq / init_ck are given,
+ * those float32 centroids (warm start, e.g. from the clustering of an earlier diffusion step;
+ * paragraph "Clustering Reuse").  Exactly one of (init_*_idx, init_c*) is needed per side; the
+ * centroid arrays win if both are given.
+ *
+ * Outputs: labels_q/labels_k [bh, n]; cq [bh, kq, d], ck [bh, kk, d] float32 = exact means of the
+ * returned labels (previous value for empty clusters); counts_q [bh, kq], counts_k [bh, kk].
+ * objective (nullable) [bh, iters, 2] float64: sum_i ||P^_i - Pbar^_{L_i}||^2 at assignment time
+ * of Step A (index 0) and Step B (index 1) -- a diagnostic, costs one extra pass per half-step.
+ * Arithmetic: assignment decisions are taken in float64 (a bf16 matrix-core pass only pre-filters
+ * tokens whose best and second-best scores are far apart); centroid means are float64 sums in a
+ * fixed order, carried in float64 between iterations and rounded to float32 on output.
+ */
+int svoo_cocluster(const svoo_shape* shape, const void* q, const void* k,
+                   const int32_t* init_q_idx, const int32_t* init_k_idx,
+                   const float* init_cq, const float* init_ck, int32_t iters,
+                   int32_t* labels_q, int32_t* labels_k, float* cq, float* ck,
+                   int32_t* counts_q, int32_t* counts_k, double* objective,
+                   void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * One assignment of Algorithm 1 on its own (the "Assign ... to blocks" line of Step A or B):
+ * x [bh, n, d] rows against own-side centroids c_own [bh, k_own, d] through the affinity to
+ * c_opp [bh, k_opp, d] (float32 both).  labels [bh, n].  k_own, k_opp <= 1024.
+ */
+int svoo_assign(const svoo_shape* shape, const void* x, const float* c_own, int32_t k_own,
+                const float* c_opp, int32_t k_opp, int32_t* labels,
+                void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Cluster-contiguous layout (the contiguous block layout block-sparse kernels need; the paper
+ * inherits it from the k-means based prior work it builds on, Sec. 2.2 / "Kernel Customization").
+ * Stable counting sort of labels [bh, n] with n_clusters bins:
+ *   perm[bh, n]               perm[p] = token stored at sorted position p (clusters ascending,
+ *                             token index ascending inside a cluster -- the order is unique)
+ *   offsets[bh, n_clusters+1] first sorted position of each cluster; offsets[n_clusters] = n
+ * then, for t < n_tensors (0..4): dst[t][b, p, :] = src[t][b, perm[b, p], :].  src/dst are HOST
+ * arrays of device pointers, each tensor [bh, n, d] of shape->dtype; dst must not alias src.
+ * Labels outside [0, n_clusters) are clamped into range.
+ */
+int svoo_permute(const svoo_shape* shape, const int32_t* labels, int32_t n_clusters,
+                 int32_t n_tensors, const void* const* src, void* const* dst,
+                 int32_t* perm, int32_t* offsets, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* dst[b, perm[b, p], :] = src_sorted[b, p, :]  (inverse of the row gather above). */
+int svoo_unpermute(const svoo_shape* shape, const void* src_sorted, const int32_t* perm, void* dst,
+                   void* hip_stream);
+
+/*
+ * Top Block-Pair Selection.  Per slice b and query block r (skipped, count 0, if counts_q[r]==0):
+ *   a_j   = scale * <cq[r], ck[j]>                      coarse estimate A_bar = C_q C_k^T
+ *   w_j   = counts_k[j] * exp(a_j - max) / Z            size-weighted softmax over non-empty key blocks
+ *   order = key blocks by w descending, equal weights by lower j
+ *   m     = shortest prefix of `order` whose cumulative w >= tau  (all non-empty blocks if tau >= 1)
+ *   b     = ceil(keep[b] * kk)                          keep = fraction of key blocks kept (budget s)
+ *   kept  = first (keep[b] > theta ? min(m, b) : max(m, b)) of `order`, clamped to [1, #non-empty]
+ * (the threshold-dependent rule of the selection paragraph; Recall(A_bar, tau) is read as m / kk).
+ * All of it in float64.  keep [bh] float32 in [0, 1] on the device; tau in (0, 1], theta any.
+ *
+ * Outputs: block_count [bh, kq]; block_list [bh, kq, kk] kept key-block ids ascending in the first
+ * block_count entries (the rest is set to -1); bitmap (nullable) [bh, kq, kk] 0/1 bytes.
+ */
+int svoo_block_mask(const svoo_shape* shape, const float* cq, const float* ck,
+                    const int32_t* counts_q, const int32_t* counts_k, const float* keep,
+                    float tau, float theta, float scale,
+                    int32_t* block_count, int32_t* block_list, uint8_t* bitmap,
+                    void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Attention over kept block pairs only: for sorted query row p in query block r,
+ *   out[p] = sum_t softmax_t(scale * <q[p], k[t]>) v[t],  t over the rows of all kept key blocks of r,
+ * the softmax normalised over those keys.  q_sorted / k_sorted / v_sorted / out_sorted [bh, n, d]
+ * in cluster order; q_offsets [bh, kq+1], k_offsets [bh, kk+1] from svoo_permute; block_count /
+ * block_list from svoo_block_mask.  lse (nullable) [bh, n] float32: log-sum-exp of the scaled
+ * logits over the kept keys (natural log).  A query block with no kept key writes zeros.
+ * bf16: both contractions on bf16 matrix cores with float32 accumulation, probabilities rounded to
+ * bf16 before the second one; f32: float32 arithmetic throughout.
+ */
+int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
+                           const void* v_sorted, const int32_t* q_offsets, const int32_t* k_offsets,
+                           const int32_t* block_count, const int32_t* block_list, float scale,
+                           void* out_sorted, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Dense attention out = softmax(scale * Q K^T) V in token order; kq, kk of the shape are ignored. */
+int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale,
+              void* out, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVOO_H */

@@ -1,0 +1,29 @@
+// Entry points that launch nothing: status strings, version, workspace sizing.
+#include "common.h"
+
+size_t cluster_ws_bytes(const svoo_shape* s);
+size_t attn_ws_bytes(const svoo_shape* s);
+
+extern "C" const char* svoo_status_string(int status) {
+    switch (status) {
+        case SVOO_OK: return "ok";
+        case SVOO_ERR_INVALID_ARG: return "invalid argument";
+        case SVOO_ERR_UNSUPPORTED: return "unsupported head dimension or dtype";
+        case SVOO_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case SVOO_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int32_t svoo_version(void) { return 100; }
+
+extern "C" size_t svoo_workspace_bytes(const svoo_shape* shape) {
+    if (check_shape(shape, true) != SVOO_OK) return 0;
+    size_t need = cluster_ws_bytes(shape);
+    const int kmax = shape->kq > shape->kk ? shape->kq : shape->kk;
+    const size_t sort_need = align_up(sort_scratch_ints(shape->bh, shape->n, kmax) * sizeof(int32_t), 256);
+    if (sort_need > need) need = sort_need;
+    const size_t attn_need = attn_ws_bytes(shape);
+    if (attn_need > need) need = attn_need;
+    return need;
+}

@@ -1,0 +1,521 @@
+// Block-sparse flash attention over kept (query block, key block) pairs, and the dense baseline.
+//
+// Work item = one tile of up to BM consecutive sorted query rows inside ONE query block r.  Its
+// keys are the rows of the kept key blocks of r, treated as one logical stream (segment after
+// segment), cut into tiles of KT keys; only the last tile of the stream is ragged.  Online softmax
+// (running max and sum per query row) makes one pass over the stream.
+//
+// bf16 kernel (CDNA4 matrix cores, v_mfma_f32_32x32x16_bf16), 4 waves x 32 query rows:
+//   S^T = K_tile Q^T      A operand: K rows from LDS, B operand: Q, resident in registers
+//   O^T += V_tile^T P^T   A operand: V^T from LDS (V is transposed while it is staged),
+//                          B operand: P^T taken straight from the S^T accumulators
+// Computing the transposes puts one query per lane: the softmax row reductions are in-lane plus a
+// single exchange between lane l and l+32, and the probabilities are already laid out as the next
+// MFMA's B operand.  The K rows are stored in LDS in the order the accumulator layout visits them
+// so that each lane ends up with 16 consecutive keys.
+//
+// f32 kernel: 4 lanes per query row, plain float32 FMAs, same schedule and key stream.
+#include "common.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+#define ATT_THREADS 256
+#define KT 64                 // keys per tile
+#define K_PITCH 272           // bytes per K row in LDS (256 + 16 pad)
+#define VT_PITCH 144          // bytes per V^T row in LDS (KT*2 + 16 pad)
+#define LOG2E 1.4426950408889634f
+
+// ---------------------------------------------------------------------------------------------
+// schedule: tile_prefix[b, r] = number of query tiles of blocks < r  (kq + 1 entries per slice)
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+attn_schedule_kernel(const int32_t* __restrict__ q_offsets, int32_t* __restrict__ tile_prefix, int kq, int bm) {
+    __shared__ int32_t scan[1024];
+    const int b = blockIdx.x, r = threadIdx.x;
+    int tiles = 0;
+    if (r < kq) {
+        const int len = q_offsets[(size_t)b * (kq + 1) + r + 1] - q_offsets[(size_t)b * (kq + 1) + r];
+        tiles = len > 0 ? (len + bm - 1) / bm : 0;
+    }
+    scan[r] = tiles;
+    __syncthreads();
+    for (int s = 1; s < 1024; s <<= 1) {
+        const int v = r >= s ? scan[r - s] : 0;
+        __syncthreads();
+        scan[r] += v;
+        __syncthreads();
+    }
+    if (r < kq) {
+        tile_prefix[(size_t)b * (kq + 1) + r] = scan[r] - tiles;
+        if (r == kq - 1) tile_prefix[(size_t)b * (kq + 1) + kq] = scan[r];
+    }
+}
+
+// Trivial one-block clustering for the dense baseline: offsets {0, n}, one kept block.
+__global__ void dense_layout_kernel(int32_t* __restrict__ offsets, int32_t* __restrict__ block_count,
+                                    int32_t* __restrict__ block_list, int n, int bh) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= bh) return;
+    offsets[2 * b] = 0;
+    offsets[2 * b + 1] = n;
+    block_count[b] = 1;
+    block_list[b] = 0;
+}
+
+struct AttnArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    void* out;
+    float* lse;
+    const int32_t* q_offsets;
+    const int32_t* k_offsets;
+    const int32_t* block_count;
+    const int32_t* block_list;
+    const int32_t* tile_prefix;
+    int n, kq, kk;
+    float scale;
+};
+
+struct TileInfo {
+    int q0, qn;    // first sorted query row of the tile, number of valid rows
+    int r;         // query block
+    int total;     // keys in the logical stream
+    int n_seg;
+};
+
+// Which tile is this workgroup?  blockIdx.x is spread round-robin over the 8 XCDs by the
+// hardware; tiles whose index differs by less than gridDim.x/8 share an XCD (and its L2) so the
+// tiles of one query block, which read the same keys, run next to each other.
+__device__ __forceinline__ int logical_tile_index() {
+    const int per_xcd = gridDim.x / 8;
+    return (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+}
+
+// Fills seg_start / seg_cum in LDS and returns the tile description; false if there is no work.
+// seg_cum has n_seg + 1 entries (exclusive prefix of segment lengths); scan is 256 ints of scratch.
+__device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* seg_start, int32_t* seg_cum,
+                                           int32_t* scan, TileInfo& ti) {
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int32_t* tp = a.tile_prefix + (size_t)b * (a.kq + 1);
+    const int slot = logical_tile_index();
+    if (slot >= tp[a.kq]) return false;
+    int lo = 0, hi = a.kq;  // last r with tp[r] <= slot
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (tp[mid] <= slot) lo = mid; else hi = mid;
+    }
+    // skip empty query blocks that share the same prefix value: take the last r with tp[r] <= slot
+    const int r = lo;
+    const int32_t* qo = a.q_offsets + (size_t)b * (a.kq + 1);
+    const int t = slot - tp[r];
+    ti.r = r;
+    ti.q0 = qo[r] + t * bm;
+    const int rem = qo[r + 1] - ti.q0;
+    ti.qn = rem < bm ? rem : bm;
+    int cnt = a.block_count[(size_t)b * a.kq + r];
+    cnt = cnt < 0 ? 0 : (cnt > a.kk ? a.kk : cnt);
+    const int32_t* bl = a.block_list + ((size_t)b * a.kq + r) * a.kk;
+    const int32_t* ko = a.k_offsets + (size_t)b * (a.kk + 1);
+    // each thread owns 4 consecutive segments
+    int len[4], start[4], local = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid * 4 + u;
+        len[u] = 0;
+        start[u] = 0;
+        if (i < cnt) {
+            int j = bl[i];
+            j = j < 0 ? 0 : (j >= a.kk ? a.kk - 1 : j);
+            start[u] = ko[j];
+            len[u] = ko[j + 1] - ko[j];
+            len[u] = len[u] < 0 ? 0 : len[u];
+        }
+        local += len[u];
+    }
+    scan[tid] = local;
+    __syncthreads();
+    for (int s = 1; s < ATT_THREADS; s <<= 1) {
+        const int v = tid >= s ? scan[tid - s] : 0;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+    }
+    int run = scan[tid] - local;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid * 4 + u;
+        if (i < cnt) {
+            seg_start[i] = start[u];
+            seg_cum[i] = run;
+        }
+        run += len[u];
+    }
+    ti.total = scan[ATT_THREADS - 1];
+    ti.n_seg = cnt;
+    if (tid == 0) seg_cum[cnt] = ti.total;
+    __syncthreads();
+    return true;
+}
+
+// Sorted key row of logical stream position p (p < total): last segment s with seg_cum[s] <= p.
+__device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_t* seg_cum, int n_seg, int p) {
+    int lo = 0, hi = n_seg;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (seg_cum[mid] <= p) lo = mid; else hi = mid;
+    }
+    return seg_start[lo] + (p - seg_cum[lo]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// bf16 matrix-core kernel, head dimension D (64 or 128), BM = 128 query rows per workgroup
+// ---------------------------------------------------------------------------------------------
+#define BM_BF16 128
+
+template <int D>
+__global__ void __launch_bounds__(ATT_THREADS)
+sparse_attn_bf16_kernel(AttnArgs a) {
+    constexpr int DC = D / 16;        // 16-wide contraction chunks of QK^T
+    constexpr int DB = D / 32;        // 32-row blocks of O^T
+    constexpr int KPITCH = D * 2 + 16;
+    __shared__ int32_t seg_start[SVOO_MAX_K];
+    __shared__ int32_t seg_cum[SVOO_MAX_K + 1];
+    __shared__ int32_t scan[ATT_THREADS];
+    __shared__ int32_t rowidx[KT];
+    __shared__ __attribute__((aligned(16))) unsigned char k_lds[KT * KPITCH];
+    __shared__ __attribute__((aligned(16))) unsigned char vt_lds[D * VT_PITCH];
+
+    TileInfo ti;
+    if (!setup_tile(a, BM_BF16, seg_start, seg_cum, scan, ti)) return;
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
+    const uint16_t* qg = (const uint16_t*)a.q + (size_t)b * a.n * D;
+    const uint16_t* kg = (const uint16_t*)a.k + (size_t)b * a.n * D;
+    const uint16_t* vg = (const uint16_t*)a.v + (size_t)b * a.n * D;
+
+    // Q fragments: query row (wave, j), contraction elements 16c + 8h .. +7
+    const int qrow = 32 * wave + j;
+    const bool qvalid = qrow < ti.qn;
+    bf16x8 qf[DC];
+    {
+        const uint4* src = (const uint4*)(qg + (size_t)(ti.q0 + (qvalid ? qrow : 0)) * D);
+#pragma unroll
+        for (int c = 0; c < DC; ++c) {
+            uint4 u = qvalid ? src[2 * c + h] : make_uint4(0, 0, 0, 0);
+            qf[c] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+    float m2 = -INFINITY;   // running max of the scaled logits, log2 domain
+    float lsum = 0.f;       // this lane's share of the running sum (its 16 keys of every 32)
+    const float c2 = a.scale * LOG2E;
+
+    const int n_tiles = (ti.total + KT - 1) / KT;
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        __syncthreads();  // previous tile fully consumed
+        if (tid < KT) {
+            const int p = kt * KT + tid;
+            rowidx[tid] = p < ti.total ? stream_row(seg_start, seg_cum, ti.n_seg, p) : -1;
+        }
+        __syncthreads();
+        // ---- stage K: 16 threads per row, 16 bytes each
+#pragma unroll
+        for (int it = 0; it < (KT * D * 2) / (ATT_THREADS * 16); ++it) {
+            constexpr int CPR = D / 8;  // 16-byte chunks per row
+            const int e = tid + it * ATT_THREADS;
+            const int row = e / CPR, chunk = e % CPR;
+            const int g = rowidx[row];
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (g >= 0) val = *(const uint4*)(kg + (size_t)g * D + chunk * 8);
+            const int key = row % 32, kb = row / 32;
+            const int mrow = 32 * kb + 8 * ((key % 16) / 4) + 4 * (key / 16) + (key % 4);
+            *(uint4*)(k_lds + mrow * KPITCH + chunk * 16) = val;
+        }
+        // ---- stage V transposed: unit = (pair of d columns, 4 consecutive keys)
+#pragma unroll
+        for (int it = 0; it < (KT / 4) * (D / 2) / ATT_THREADS; ++it) {
+            const int u = tid + it * ATT_THREADS;
+            const int wunit = u / 64;                 // wave-sized unit
+            const int dpl = lane % 16, kgl = lane / 16;
+            constexpr int DPB = D / 32;               // blocks of 16 d-pairs
+            const int dp = (wunit % DPB) * 16 + dpl;
+            const int kgrp = (wunit / DPB) * 4 + kgl;
+            uint32_t rr[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int g = rowidx[kgrp * 4 + e];
+                rr[e] = g >= 0 ? *(const uint32_t*)(vg + (size_t)g * D + 2 * dp) : 0u;
+            }
+            uint2 lo, hi;
+            lo.x = (rr[0] & 0xffffu) | (rr[1] << 16);
+            lo.y = (rr[2] & 0xffffu) | (rr[3] << 16);
+            hi.x = (rr[0] >> 16) | (rr[1] & 0xffff0000u);
+            hi.y = (rr[2] >> 16) | (rr[3] & 0xffff0000u);
+            *(uint2*)(vt_lds + (2 * dp) * VT_PITCH + kgrp * 8) = lo;
+            *(uint2*)(vt_lds + (2 * dp + 1) * VT_PITCH + kgrp * 8) = hi;
+        }
+        __syncthreads();
+
+        // ---- S^T = K Q^T for the two 32-key blocks of the tile
+        f32x16 s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+#pragma unroll
+            for (int c = 0; c < DC; ++c) {
+                const uint4 u = *(const uint4*)(k_lds + (32 * kb + j) * KPITCH + c * 32 + h * 16);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, u), qf[c], s[kb], 0, 0, 0);
+            }
+        }
+        // lane (j, h) now holds, for query j, keys 32*kb + 16*h + v  (v = accumulator index)
+        const int key_base = kt * KT + 16 * h;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float x = s[kb][v] * c2;
+                if (key_base + 32 * kb + v >= ti.total) x = -INFINITY;
+                s[kb][v] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m2, mx);
+        const float alpha = exp2f(m2 - m_new);   // m2 = -inf on the first tile gives 0
+        m2 = m_new;
+        lsum *= alpha;
+        bf16x8 pf[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float p0 = exp2f(s[kb][8 * t + 2 * e] - m_new);
+                    const float p1 = exp2f(s[kb][8 * t + 2 * e + 1] - m_new);
+                    lsum += p0 + p1;
+                    w[e] = pack_bf16x2(p0, p1);
+                }
+                pf[kb][t] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            }
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const uint4 u = *(const uint4*)(vt_lds + (32 * db + j) * VT_PITCH + (32 * kb + 16 * h + 8 * t) * 2);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, u), pf[kb][t], o[db], 0,
+                                                                    0, 0);
+                }
+    }
+
+    // ---- epilogue: normalise and store.  Lane (j, h) holds O[q = j][d = 32 db + 8 (v/4) + 4 h + v%4].
+    const float ltot = lsum + __shfl_xor(lsum, 32);
+    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    if (qvalid) {
+        uint16_t* og = (uint16_t*)a.out + ((size_t)b * a.n + ti.q0 + qrow) * D;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint2 w;
+                w.x = pack_bf16x2(o[db][4 * g] * inv, o[db][4 * g + 1] * inv);
+                w.y = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+                *(uint2*)(og + 32 * db + 8 * g + 4 * h) = w;
+            }
+        if (a.lse && h == 0)
+            a.lse[(size_t)b * a.n + ti.q0 + qrow] = ltot > 0.f ? (m2 + log2f(ltot)) * 0.6931471805599453f : -INFINITY;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// float32 kernel: 64 query rows per workgroup, 4 lanes per row, each lane owns D/4 columns
+// (interleaved in groups of 4: lane part p owns columns 16 c + 4 p .. +3), keys staged 32 at a time
+// ---------------------------------------------------------------------------------------------
+#define BM_F32 64
+#define KT_F32 32
+
+template <int D>
+__global__ void __launch_bounds__(ATT_THREADS)
+sparse_attn_f32_kernel(AttnArgs a) {
+    constexpr int NC = D / 16;  // float4 chunks per lane
+    __shared__ int32_t seg_start[SVOO_MAX_K];
+    __shared__ int32_t seg_cum[SVOO_MAX_K + 1];
+    __shared__ int32_t scan[ATT_THREADS];
+    __shared__ int32_t rowidx[KT_F32];
+    __shared__ float4 k_lds[KT_F32 * D / 4];
+    __shared__ float4 v_lds[KT_F32 * D / 4];
+
+    TileInfo ti;
+    if (!setup_tile(a, BM_F32, seg_start, seg_cum, scan, ti)) return;
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int qrow = tid / 4, part = tid % 4;
+    const bool qvalid = qrow < ti.qn;
+    const float4* qg = (const float4*)a.q + (size_t)b * a.n * (D / 4);
+    const float4* kg = (const float4*)a.k + (size_t)b * a.n * (D / 4);
+    const float4* vg = (const float4*)a.v + (size_t)b * a.n * (D / 4);
+    float4 qv[NC], ov[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        qv[c] = qvalid ? qg[(size_t)(ti.q0 + qrow) * (D / 4) + 4 * c + part] : make_float4(0, 0, 0, 0);
+        ov[c] = make_float4(0, 0, 0, 0);
+    }
+    float m = -INFINITY, lsum = 0.f;
+    const int n_tiles = (ti.total + KT_F32 - 1) / KT_F32;
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        __syncthreads();
+        if (tid < KT_F32) {
+            const int p = kt * KT_F32 + tid;
+            rowidx[tid] = p < ti.total ? stream_row(seg_start, seg_cum, ti.n_seg, p) : -1;
+        }
+        __syncthreads();
+        for (int e = tid; e < KT_F32 * D / 4; e += ATT_THREADS) {
+            const int row = e / (D / 4), col = e % (D / 4);
+            const int g = rowidx[row];
+            k_lds[e] = g >= 0 ? kg[(size_t)g * (D / 4) + col] : make_float4(0, 0, 0, 0);
+            v_lds[e] = g >= 0 ? vg[(size_t)g * (D / 4) + col] : make_float4(0, 0, 0, 0);
+        }
+        __syncthreads();
+        const int valid = ti.total - kt * KT_F32 < KT_F32 ? ti.total - kt * KT_F32 : KT_F32;
+        float sc[KT_F32];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int key = 0; key < KT_F32; ++key) {
+            float s = 0.f;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 kv = k_lds[key * (D / 4) + 4 * c + part];
+                s = fmaf(qv[c].x, kv.x, s);
+                s = fmaf(qv[c].y, kv.y, s);
+                s = fmaf(qv[c].z, kv.z, s);
+                s = fmaf(qv[c].w, kv.w, s);
+            }
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            s = key < valid ? s * a.scale : -INFINITY;
+            sc[key] = s;
+            mx = fmaxf(mx, s);
+        }
+        const float m_new = fmaxf(m, mx);
+        const float alpha = expf(m - m_new);
+        m = m_new;
+        lsum *= alpha;
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            ov[c].x *= alpha;
+            ov[c].y *= alpha;
+            ov[c].z *= alpha;
+            ov[c].w *= alpha;
+        }
+#pragma unroll
+        for (int key = 0; key < KT_F32; ++key) {
+            const float p = expf(sc[key] - m_new);
+            lsum += p;
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const float4 vv = v_lds[key * (D / 4) + 4 * c + part];
+                ov[c].x = fmaf(p, vv.x, ov[c].x);
+                ov[c].y = fmaf(p, vv.y, ov[c].y);
+                ov[c].z = fmaf(p, vv.z, ov[c].z);
+                ov[c].w = fmaf(p, vv.w, ov[c].w);
+            }
+        }
+    }
+    if (qvalid) {
+        const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+        float4* og = (float4*)a.out + ((size_t)b * a.n + ti.q0 + qrow) * (D / 4);
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            og[4 * c + part] = make_float4(ov[c].x * inv, ov[c].y * inv, ov[c].z * inv, ov[c].w * inv);
+        if (a.lse && part == 0) a.lse[(size_t)b * a.n + ti.q0 + qrow] = lsum > 0.f ? m + logf(lsum) : -INFINITY;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static inline int attn_bm(int dtype) { return dtype == SVOO_BF16 ? BM_BF16 : BM_F32; }
+
+size_t attn_ws_bytes(const svoo_shape* s) {
+    // tile_prefix for the sparse call; the dense call adds a 1-block layout
+    const size_t kq = s->kq > 1 ? s->kq : 1;
+    return align_up((size_t)s->bh * (kq + 1) * 4, 256) + 3 * align_up((size_t)s->bh * 2 * 4, 256);
+}
+
+static int launch_sparse(const svoo_shape* s, AttnArgs& a, int32_t* tile_prefix, hipStream_t stream) {
+    const int bm = attn_bm(s->dtype);
+    hipLaunchKernelGGL(attn_schedule_kernel, dim3(s->bh), dim3(1024), 0, stream, a.q_offsets, tile_prefix, a.kq, bm);
+    a.tile_prefix = tile_prefix;
+    int gx = (s->n + bm - 1) / bm + a.kq;
+    gx = (gx + 7) / 8 * 8;
+    dim3 grid(gx, s->bh);
+    if (s->dtype == SVOO_BF16) {
+        if (s->d == 128)
+            hipLaunchKernelGGL(sparse_attn_bf16_kernel<128>, grid, dim3(ATT_THREADS), 0, stream, a);
+        else
+            hipLaunchKernelGGL(sparse_attn_bf16_kernel<64>, grid, dim3(ATT_THREADS), 0, stream, a);
+    } else {
+        if (s->d == 128)
+            hipLaunchKernelGGL(sparse_attn_f32_kernel<128>, grid, dim3(ATT_THREADS), 0, stream, a);
+        else
+            hipLaunchKernelGGL(sparse_attn_f32_kernel<64>, grid, dim3(ATT_THREADS), 0, stream, a);
+    }
+    return launch_status();
+}
+
+extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
+                                      const void* v_sorted, const int32_t* q_offsets, const int32_t* k_offsets,
+                                      const int32_t* block_count, const int32_t* block_list, float scale,
+                                      void* out_sorted, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
+    int st = check_shape(shape, true);
+    if (st != SVOO_OK) return st;
+    if (!q_sorted || !k_sorted || !v_sorted || !q_offsets || !k_offsets || !block_count || !block_list ||
+        !out_sorted || !ws)
+        return SVOO_ERR_INVALID_ARG;
+    if (!aligned16(q_sorted) || !aligned16(k_sorted) || !aligned16(v_sorted) || !aligned16(out_sorted) ||
+        (((uintptr_t)ws) & 255u) != 0)
+        return SVOO_ERR_INVALID_ARG;
+    if (!(scale == scale) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    if (ws_bytes < attn_ws_bytes(shape)) return SVOO_ERR_WORKSPACE_TOO_SMALL;
+    AttnArgs a = {q_sorted, k_sorted, v_sorted, out_sorted, lse, q_offsets, k_offsets, block_count, block_list,
+                  nullptr, shape->n, shape->kq, shape->kk, scale};
+    return launch_sparse(shape, a, (int32_t*)ws, (hipStream_t)hip_stream);
+}
+
+extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale, void* out,
+                         float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
+    int st = check_shape(shape, false);
+    if (st != SVOO_OK) return st;
+    if (!q || !k || !v || !out || !ws) return SVOO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (((uintptr_t)ws) & 255u) != 0)
+        return SVOO_ERR_INVALID_ARG;
+    if (!(scale == scale) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    svoo_shape s = *shape;
+    s.kq = 1;
+    s.kk = 1;
+    if (ws_bytes < attn_ws_bytes(&s)) return SVOO_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    WsCarver c(ws);
+    int32_t* tile_prefix = c.take<int32_t>((size_t)s.bh * 2);
+    int32_t* offsets = c.take<int32_t>((size_t)s.bh * 2);
+    int32_t* block_count = c.take<int32_t>((size_t)s.bh);
+    int32_t* block_list = c.take<int32_t>((size_t)s.bh);
+    hipLaunchKernelGGL(dense_layout_kernel, dim3((s.bh + 255) / 256), dim3(256), 0, stream, offsets, block_count,
+                       block_list, s.n, s.bh);
+    AttnArgs a = {q, k, v, out, lse, offsets, offsets, block_count, block_list, nullptr, s.n, 1, 1, scale};
+    return launch_sparse(&s, a, tile_prefix, stream);
+}

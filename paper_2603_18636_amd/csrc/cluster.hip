@@ -1,0 +1,593 @@
+// Bidirectional co-clustering (Algorithm 1): assignment, centroid update and the driver loop.
+//
+// Assignment of one side ("own") against the other ("opp").  Algorithm 1 asks for
+//   L_i = argmin_j || Norm(x_i C_opp^T) - Norm(c_own_j C_opp^T) ||_2 .
+// With row-wise L2 Norm, p^ = P / nx (nx = max(||P||, eps)) and pbar^_j the normalised anchor row,
+//   ||p^ - pbar^_j||^2 = ||p^||^2 + b_j - 2 <x, W_j> / nx ,   W_j = C_opp^T pbar^_j ,  b_j = ||pbar^_j||^2
+// so the N x K_opp affinity matrix never has to exist: W (K_own x d) is built once per half-step
+// and every token needs one d-length dot product per own-side centroid.  b_j is exactly 1 unless
+// ||c_own_j C_opp^T|| < eps (a degenerate anchor, e.g. an all-zero centroid); slices without
+// such anchors reduce to argmax_j <x, W_j>.  Slices with one take the general form, which needs
+// nx^2 = x^T (C_opp^T C_opp) x per token.
+//
+// Every decision is taken in float64: tokens are exact in float64, W is float64, accumulation is
+// float64 in a fixed order.
+#include "common.h"
+
+#define NORM_FLOOR 1e-12
+
+// ---------------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------------
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, size_t count) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = v;
+}
+
+template <typename T>
+__device__ __forceinline__ double load_as_f64(const T* p);
+template <>
+__device__ __forceinline__ double load_as_f64<uint16_t>(const uint16_t* p) { return (double)bf16_to_f32(*p); }
+template <>
+__device__ __forceinline__ double load_as_f64<float>(const float* p) { return (double)*p; }
+
+// c64[b, c, :] = x[b, idx[b, c], :]   or   c64 = (double) init_c
+template <typename T>
+__global__ void init_centroids_kernel(const T* __restrict__ x, const int32_t* __restrict__ idx,
+                                      const float* __restrict__ init_c, double* __restrict__ c64, int n, int k,
+                                      int d) {
+    const int b = blockIdx.y, c = blockIdx.x, t = threadIdx.x;
+    if (t >= d) return;
+    double v;
+    if (init_c) {
+        v = (double)init_c[((size_t)b * k + c) * d + t];
+    } else {
+        int i = idx[(size_t)b * k + c];
+        i = i < 0 ? 0 : (i >= n ? n - 1 : i);
+        v = load_as_f64<T>(x + ((size_t)b * n + i) * d + t);
+    }
+    c64[((size_t)b * k + c) * d + t] = v;
+}
+
+__global__ void f64_to_f32_kernel(const double* __restrict__ src, float* __restrict__ dst, size_t count) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = (float)src[i];
+}
+
+__global__ void f32_to_f64_kernel(const float* __restrict__ src, double* __restrict__ dst, size_t count) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = (double)src[i];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small batched float64 GEMM with arbitrary strides: C[m, n] = sum_k A(m, k) * B(k, n).
+// 32 x 32 output tile per workgroup, 2 x 2 per thread, contraction in steps of 16 in index order.
+// Used for Pbar = C_own C_opp^T, W = Pbar^ C_opp and G = C_opp^T C_opp (all tiny next to the
+// token-sized work).
+// ---------------------------------------------------------------------------------------------
+struct GemmArgs {
+    const double* a;
+    const double* b;
+    double* c;
+    int m, n, k;
+    long long a_batch, b_batch, c_batch;
+    int a_sm, a_sk, b_sk, b_sn;
+};
+
+__global__ void __launch_bounds__(256) gemm_f64_kernel(GemmArgs g) {
+    __shared__ double as[16][33];
+    __shared__ double bs[16][33];
+    const double* a = g.a + (size_t)blockIdx.z * g.a_batch;
+    const double* b = g.b + (size_t)blockIdx.z * g.b_batch;
+    double* c = g.c + (size_t)blockIdx.z * g.c_batch;
+    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    double acc[2][2] = {{0, 0}, {0, 0}};
+    for (int k0 = 0; k0 < g.k; k0 += 16) {
+        for (int e = threadIdx.x; e < 512; e += 256) {
+            const int kk = e % 16, r = e / 16;
+            const int m = m0 + r, n = n0 + r, k = k0 + kk;
+            as[kk][r] = (m < g.m && k < g.k) ? a[(size_t)m * g.a_sm + (size_t)k * g.a_sk] : 0.0;
+            bs[kk][r] = (n < g.n && k < g.k) ? b[(size_t)k * g.b_sk + (size_t)n * g.b_sn] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const double a0 = as[kk][ty * 2], a1 = as[kk][ty * 2 + 1];
+            const double b0 = bs[kk][tx * 2], b1 = bs[kk][tx * 2 + 1];
+            acc[0][0] = fma(a0, b0, acc[0][0]);
+            acc[0][1] = fma(a0, b1, acc[0][1]);
+            acc[1][0] = fma(a1, b0, acc[1][0]);
+            acc[1][1] = fma(a1, b1, acc[1][1]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {
+            const int m = m0 + ty * 2 + i, n = n0 + tx * 2 + j;
+            if (m < g.m && n < g.n) c[(size_t)m * g.n + n] = acc[i][j];
+        }
+}
+
+static void launch_gemm(const GemmArgs& g, int batch, hipStream_t stream) {
+    dim3 grid((g.n + 31) / 32, (g.m + 31) / 32, batch);
+    hipLaunchKernelGGL(gemm_f64_kernel, grid, dim3(256), 0, stream, g);
+}
+
+// Row-wise L2 normalisation of Pbar [bh, k_own, k_opp] in place; b_j and the degenerate flag.
+__global__ void __launch_bounds__(256)
+normalize_anchor_rows_kernel(double* __restrict__ pbar, double* __restrict__ bterm, int32_t* __restrict__ flags,
+                             int k_own, int k_opp) {
+    __shared__ double red[256];
+    const int b = blockIdx.y, j = blockIdx.x, t = threadIdx.x;
+    double* row = pbar + ((size_t)b * k_own + j) * k_opp;
+    double s = 0.0;
+    for (int c = t; c < k_opp; c += 256) s = fma(row[c], row[c], s);
+    red[t] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (t < w) red[t] += red[t + w];
+        __syncthreads();
+    }
+    const double nrm = sqrt(red[0]);
+    const double div = nrm > NORM_FLOOR ? nrm : NORM_FLOOR;
+    for (int c = t; c < k_opp; c += 256) row[c] = row[c] / div;
+    if (t == 0) {
+        const bool degenerate = !(nrm >= NORM_FLOOR);
+        const double r = nrm / NORM_FLOOR;
+        bterm[(size_t)b * k_own + j] = degenerate ? r * r : 1.0;
+        if (degenerate) atomicOr(&flags[b], 1);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Tiled float64 contraction of a 64-token tile against the rows of a matrix B [rows_b, D]:
+//   MODE_ARGMAX    B = W; per token the row j maximising the score, lowest j on ties
+//   MODE_QUADFORM  B = G (D x D, symmetric); per token x^T G x
+// 256 threads = 16 x 16; thread (ty, tx) owns tokens 4ty..4ty+3 and B rows 4tx..4tx+3 of the
+// current 64-row block.  The token tile stays in LDS as float64 for the whole kernel.
+// ---------------------------------------------------------------------------------------------
+enum { MODE_ARGMAX = 0, MODE_QUADFORM = 1 };
+
+template <typename T, int D, int MODE>
+__global__ void __launch_bounds__(256)
+token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int rows_b,
+                  const double* __restrict__ bterm, const int32_t* __restrict__ flags,
+                  const double* __restrict__ nx2, const int32_t* __restrict__ list,
+                  const int32_t* __restrict__ list_count, int32_t force_general, int32_t* __restrict__ labels,
+                  double* __restrict__ quad_out, int n) {
+    extern __shared__ double smem[];
+    double* xs = smem;                 // [D][65]
+    double* ws = smem + D * 65;        // [16][65]
+    double* red_s = ws + 16 * 65;      // [64][16]
+    int32_t* red_j = (int32_t*)(red_s + 64 * 16);  // [64][16]
+    int32_t* tok = red_j + 64 * 16;    // [64]
+
+    const int b = blockIdx.y;
+    const int t0 = blockIdx.x * 64;
+    const int count = list ? list_count[b] : n;
+    if (t0 >= count) return;
+    // nx^2 is only consumed by slices with a degenerate anchor unless the caller forces it
+    if (MODE == MODE_QUADFORM && !force_general && flags[b] == 0) return;
+    const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    if (tid < 64) {
+        const int p = t0 + tid;
+        tok[tid] = p < count ? (list ? list[(size_t)b * n + p] : p) : -1;
+    }
+    __syncthreads();
+    // stage the token tile: thread -> token tid/4, elements part*4 .. +3 of every 16-chunk
+    {
+        const int token = tid / 4, part = tid % 4;
+        const int ti = tok[token];
+        const T* src = x + ((size_t)b * n + (ti < 0 ? 0 : ti)) * D;
+        for (int kc = 0; kc < D; kc += 16)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int col = kc + part * 4 + e;
+                xs[col * 65 + token] = ti < 0 ? 0.0 : load_as_f64<T>(src + col);
+            }
+    }
+    const bool general = MODE == MODE_ARGMAX && (force_general || flags[b] != 0);
+    double nx_tok[4] = {0, 0, 0, 0};
+    if (general) {
+        for (int a = 0; a < 4; ++a) {
+            const int ti = tok[ty * 4 + a];
+            const double v = ti < 0 ? 0.0 : nx2[(size_t)b * n + ti];
+            const double r = sqrt(v > 0.0 ? v : 0.0);
+            nx_tok[a] = r > NORM_FLOOR ? r : NORM_FLOOR;
+        }
+    }
+    double best[4];
+    int bestj[4] = {0, 0, 0, 0};
+    double quad[4] = {0, 0, 0, 0};
+    for (int a = 0; a < 4; ++a) best[a] = -INFINITY;
+    const double* bm = bmat + (size_t)b * rows_b * D;
+    const double* bt = bterm ? bterm + (size_t)b * rows_b : nullptr;
+
+    for (int r0 = 0; r0 < rows_b; r0 += 64) {
+        double acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[a][e] = 0.0;
+        for (int kc = 0; kc < D; kc += 16) {
+            __syncthreads();
+            {
+                const int row = tid / 4, part = tid % 4;
+                const int j = r0 + row;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    ws[(part * 4 + e) * 65 + row] = j < rows_b ? bm[(size_t)j * D + kc + part * 4 + e] : 0.0;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) {
+                double xa[4], wb[4];
+#pragma unroll
+                for (int a = 0; a < 4; ++a) xa[a] = xs[(kc + kk) * 65 + ty * 4 + a];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) wb[e] = ws[kk * 65 + tx * 4 + e];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[a][e] = fma(xa[a], wb[e], acc[a][e]);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = r0 + tx * 4 + e;
+            if (j < rows_b) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    if (MODE == MODE_ARGMAX) {
+                        const double val = general ? 2.0 * acc[a][e] - nx_tok[a] * bt[j] : acc[a][e];
+                        if (val > best[a]) {
+                            best[a] = val;
+                            bestj[a] = j;
+                        }
+                    } else {
+                        quad[a] = fma(acc[a][e], xs[j * 65 + ty * 4 + a], quad[a]);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int a = 0; a < 4; ++a) {
+        red_s[(ty * 4 + a) * 16 + tx] = MODE == MODE_ARGMAX ? best[a] : quad[a];
+        red_j[(ty * 4 + a) * 16 + tx] = bestj[a];
+    }
+    __syncthreads();
+    if (tid < 64 && tok[tid] >= 0) {
+        if (MODE == MODE_ARGMAX) {
+            double bv = red_s[tid * 16];
+            int bj = red_j[tid * 16];
+            for (int u = 1; u < 16; ++u) {
+                const double v = red_s[tid * 16 + u];
+                const int j = red_j[tid * 16 + u];
+                if (v > bv || (v == bv && j < bj)) {
+                    bv = v;
+                    bj = j;
+                }
+            }
+            labels[(size_t)b * n + tok[tid]] = bj;
+        } else {
+            double s = 0.0;
+            for (int u = 0; u < 16; ++u) s += red_s[tid * 16 + u];
+            quad_out[(size_t)b * n + tok[tid]] = s;
+        }
+    }
+}
+
+template <int D>
+static constexpr size_t token_tile_lds() {
+    return (size_t)(D * 65 + 16 * 65 + 64 * 16) * sizeof(double) + (64 * 16 + 64) * sizeof(int32_t);
+}
+
+template <typename T, int D, int MODE>
+static void launch_token_tile(const T* x, const double* bmat, int rows_b, const double* bterm, const int32_t* flags,
+                              const double* nx2, const int32_t* list, const int32_t* list_count, int force_general,
+                              int32_t* labels, double* quad_out, int bh, int n, hipStream_t stream) {
+    auto kern = token_tile_kernel<T, D, MODE>;
+    // more than 64 KB of dynamic LDS has to be opted into per kernel (per device, so not cached here)
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)token_tile_lds<D>()) != hipSuccess)
+        return;
+    dim3 grid((n + 63) / 64, bh);
+    hipLaunchKernelGGL(kern, grid, dim3(256), token_tile_lds<D>(), stream, x, bmat, rows_b, bterm, flags, nx2, list,
+                       list_count, force_general, labels, quad_out, n);
+}
+
+template <int MODE>
+static void dispatch_token_tile(const svoo_shape* s, const void* x, const double* bmat, int rows_b,
+                                const double* bterm, const int32_t* flags, const double* nx2, const int32_t* list,
+                                const int32_t* list_count, int force_general, int32_t* labels, double* quad_out,
+                                hipStream_t stream) {
+    if (s->dtype == SVOO_BF16) {
+        if (s->d == 128)
+            launch_token_tile<uint16_t, 128, MODE>((const uint16_t*)x, bmat, rows_b, bterm, flags, nx2, list,
+                                                   list_count, force_general, labels, quad_out, s->bh, s->n, stream);
+        else
+            launch_token_tile<uint16_t, 64, MODE>((const uint16_t*)x, bmat, rows_b, bterm, flags, nx2, list,
+                                                  list_count, force_general, labels, quad_out, s->bh, s->n, stream);
+    } else {
+        if (s->d == 128)
+            launch_token_tile<float, 128, MODE>((const float*)x, bmat, rows_b, bterm, flags, nx2, list, list_count,
+                                                force_general, labels, quad_out, s->bh, s->n, stream);
+        else
+            launch_token_tile<float, 64, MODE>((const float*)x, bmat, rows_b, bterm, flags, nx2, list, list_count,
+                                               force_general, labels, quad_out, s->bh, s->n, stream);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Centroid update: C[j] = mean of the member rows, float64 sums in a fixed order.
+// One workgroup per (cluster, slice); members are perm[offsets[j] .. offsets[j+1]) in ascending
+// token order.  256 threads = G row-groups of (D/2) lanes; lane l adds elements 2l, 2l+1 of the
+// rows g, g+G, g+2G, ... of its group, then the G partial sums are added in group order.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void load_pair(const T* p, double& a, double& b);
+template <>
+__device__ __forceinline__ void load_pair<uint16_t>(const uint16_t* p, double& a, double& b) {
+    const uint32_t u = *(const uint32_t*)p;
+    a = (double)__uint_as_float(u << 16);
+    b = (double)__uint_as_float(u & 0xffff0000u);
+}
+template <>
+__device__ __forceinline__ void load_pair<float>(const float* p, double& a, double& b) {
+    const float2 u = *(const float2*)p;
+    a = (double)u.x;
+    b = (double)u.y;
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm,
+                       const int32_t* __restrict__ offsets, double* __restrict__ c64, float* __restrict__ c32,
+                       int32_t* __restrict__ counts, int n, int k) {
+    constexpr int LANES = D / 2;
+    constexpr int GROUPS = 256 / LANES;
+    __shared__ double part[GROUPS][D];
+    const int b = blockIdx.y, j = blockIdx.x;
+    const int lane = threadIdx.x % LANES, grp = threadIdx.x / LANES;
+    const int beg = offsets[(size_t)b * (k + 1) + j], end = offsets[(size_t)b * (k + 1) + j + 1];
+    const int32_t* pm = perm + (size_t)b * n;
+    const T* xb = x + (size_t)b * n * D;
+    double s0 = 0.0, s1 = 0.0;
+    int p = beg + grp;
+    for (; p + 3 * GROUPS < end; p += 4 * GROUPS) {
+        double a[4], c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load_pair<T>(xb + (size_t)pm[p + u * GROUPS] * D + 2 * lane, a[u], c[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            s0 += a[u];
+            s1 += c[u];
+        }
+    }
+    for (; p < end; p += GROUPS) {
+        double a, c;
+        load_pair<T>(xb + (size_t)pm[p] * D + 2 * lane, a, c);
+        s0 += a;
+        s1 += c;
+    }
+    part[grp][2 * lane] = s0;
+    part[grp][2 * lane + 1] = s1;
+    __syncthreads();
+    const int cnt = end - beg;
+    if (threadIdx.x < D) {
+        const size_t o = ((size_t)b * k + j) * D + threadIdx.x;
+        if (cnt > 0) {
+            double s = part[0][threadIdx.x];
+            for (int g = 1; g < GROUPS; ++g) s += part[g][threadIdx.x];
+            c64[o] = s / (double)cnt;
+        }
+        if (c32) c32[o] = (float)c64[o];
+    }
+    if (threadIdx.x == 0 && counts) counts[(size_t)b * k + j] = cnt;
+}
+
+static void launch_centroid_update(const svoo_shape* s, const void* x, const int32_t* perm, const int32_t* offsets,
+                                   double* c64, float* c32, int32_t* counts, int k, hipStream_t stream) {
+    dim3 grid(k, s->bh);
+    if (s->dtype == SVOO_BF16) {
+        if (s->d == 128)
+            hipLaunchKernelGGL((centroid_update_kernel<uint16_t, 128>), grid, dim3(256), 0, stream, (const uint16_t*)x,
+                               perm, offsets, c64, c32, counts, s->n, k);
+        else
+            hipLaunchKernelGGL((centroid_update_kernel<uint16_t, 64>), grid, dim3(256), 0, stream, (const uint16_t*)x,
+                               perm, offsets, c64, c32, counts, s->n, k);
+    } else {
+        if (s->d == 128)
+            hipLaunchKernelGGL((centroid_update_kernel<float, 128>), grid, dim3(256), 0, stream, (const float*)x, perm,
+                               offsets, c64, c32, counts, s->n, k);
+        else
+            hipLaunchKernelGGL((centroid_update_kernel<float, 64>), grid, dim3(256), 0, stream, (const float*)x, perm,
+                               offsets, c64, c32, counts, s->n, k);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Objective (diagnostic): D_i = ||p^_i||^2 + b_L - 2 <x_i, W_L> / nx_i, summed per slice in a
+// fixed order.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+objective_terms_kernel(const T* __restrict__ x, const double* __restrict__ w, const double* __restrict__ bterm,
+                       const double* __restrict__ nx2, const int32_t* __restrict__ labels,
+                       double* __restrict__ terms, int n, int k_own, int d) {
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int l = labels[(size_t)b * n + i];
+    const T* xr = x + ((size_t)b * n + i) * d;
+    const double* wr = w + ((size_t)b * k_own + l) * d;
+    double s = 0.0;
+    for (int c = 0; c < d; ++c) s = fma(load_as_f64<T>(xr + c), wr[c], s);
+    const double v = nx2[(size_t)b * n + i];
+    const double r = sqrt(v > 0.0 ? v : 0.0);
+    const double nx = r > NORM_FLOOR ? r : NORM_FLOOR;
+    const double pn2 = (r * r) / (nx * nx);
+    terms[(size_t)b * n + i] = pn2 + bterm[(size_t)b * k_own + l] - 2.0 * s / nx;
+}
+
+__global__ void __launch_bounds__(1024)
+objective_sum_kernel(const double* __restrict__ terms, double* __restrict__ out, int n, int out_stride) {
+    __shared__ double red[1024];
+    const int b = blockIdx.x, t = threadIdx.x;
+    double s = 0.0;
+    for (int i = t; i < n; i += 1024) s += terms[(size_t)b * n + i];
+    red[t] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if (t < w) red[t] += red[t + w];
+        __syncthreads();
+    }
+    if (t == 0) out[(size_t)b * out_stride] = red[0];
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct ClusterWs {
+    double *c64q, *c64k, *w64, *pbar, *gram, *bterm, *nx2, *terms;
+    int32_t *flags, *perm, *offsets, *chunk_hist;
+    size_t bytes;
+};
+
+static ClusterWs carve_cluster_ws(const svoo_shape* s, void* ws) {
+    WsCarver c(ws);
+    ClusterWs w;
+    const size_t bh = s->bh, kmax = s->kq > s->kk ? s->kq : s->kk;
+    w.c64q = c.take<double>(bh * s->kq * s->d);
+    w.c64k = c.take<double>(bh * s->kk * s->d);
+    w.w64 = c.take<double>(bh * kmax * s->d);
+    w.pbar = c.take<double>(bh * (size_t)s->kq * s->kk);
+    w.gram = c.take<double>(bh * (size_t)s->d * s->d);
+    w.bterm = c.take<double>(bh * kmax);
+    w.nx2 = c.take<double>(bh * (size_t)s->n);
+    w.terms = c.take<double>(bh * (size_t)s->n);
+    w.flags = c.take<int32_t>(bh);
+    w.perm = c.take<int32_t>(bh * (size_t)s->n);
+    w.offsets = c.take<int32_t>(bh * (kmax + 1));
+    w.chunk_hist = c.take<int32_t>(sort_scratch_ints(s->bh, s->n, (int)kmax));
+    w.bytes = c.used;
+    return w;
+}
+
+size_t cluster_ws_bytes(const svoo_shape* s) { return carve_cluster_ws(s, nullptr).bytes; }
+
+// One half-step's assignment: labels of x against own-side centroids through opp-side anchors.
+// want_nx2: also fill w.nx2 (needed for the objective) even if no anchor is degenerate.
+static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, const double* c_own, int k_own,
+                       const double* c_opp, int k_opp, int32_t* labels, bool want_nx2, hipStream_t stream) {
+    const int d = s->d, bh = s->bh;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((bh + 255) / 256), dim3(256), 0, stream, w.flags, 0, (size_t)bh);
+    // Pbar[j, c] = <c_own_j, c_opp_c>
+    GemmArgs g1 = {c_own, c_opp, w.pbar, k_own, k_opp, d, (long long)k_own * d, (long long)k_opp * d,
+                   (long long)k_own * k_opp, d, 1, 1, d};
+    launch_gemm(g1, bh, stream);
+    hipLaunchKernelGGL(normalize_anchor_rows_kernel, dim3(k_own, bh), dim3(256), 0, stream, w.pbar, w.bterm, w.flags,
+                       k_own, k_opp);
+    // W[j, :] = sum_c Pbar^[j, c] * c_opp[c, :]
+    GemmArgs g2 = {w.pbar, c_opp, w.w64, k_own, d, k_opp, (long long)k_own * k_opp, (long long)k_opp * d,
+                   (long long)k_own * d, k_opp, 1, d, 1};
+    launch_gemm(g2, bh, stream);
+    // G[a, b] = sum_c c_opp[c, a] * c_opp[c, b]
+    GemmArgs g3 = {c_opp, c_opp, w.gram, d, d, k_opp, (long long)k_opp * d, (long long)k_opp * d, (long long)d * d,
+                   1, d, d, 1};
+    launch_gemm(g3, bh, stream);
+    // nx^2 = x^T G x: every workgroup of a slice without degenerate anchors exits at once unless the
+    // objective wants it, so the launch sequence never depends on device-side flags.
+    dispatch_token_tile<MODE_QUADFORM>(s, x, w.gram, d, nullptr, w.flags, nullptr, nullptr, nullptr, want_nx2 ? 1 : 0,
+                                       nullptr, w.nx2, stream);
+    dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels, nullptr,
+                                     stream);
+    return launch_status();
+}
+
+static void launch_objective(const svoo_shape* s, const ClusterWs& w, const void* x, int k_own,
+                             const int32_t* labels, double* out, int out_stride, hipStream_t stream) {
+    dim3 grid((s->n + 255) / 256, s->bh);
+    if (s->dtype == SVOO_BF16)
+        hipLaunchKernelGGL(objective_terms_kernel<uint16_t>, grid, dim3(256), 0, stream, (const uint16_t*)x, w.w64,
+                           w.bterm, w.nx2, labels, w.terms, s->n, k_own, s->d);
+    else
+        hipLaunchKernelGGL(objective_terms_kernel<float>, grid, dim3(256), 0, stream, (const float*)x, w.w64, w.bterm,
+                           w.nx2, labels, w.terms, s->n, k_own, s->d);
+    hipLaunchKernelGGL(objective_sum_kernel, dim3(s->bh), dim3(1024), 0, stream, w.terms, out, s->n, out_stride);
+}
+
+static void launch_init_centroids(const svoo_shape* s, const void* x, const int32_t* idx, const float* init_c,
+                                  double* c64, int k, hipStream_t stream) {
+    dim3 grid(k, s->bh);
+    if (s->dtype == SVOO_BF16)
+        hipLaunchKernelGGL(init_centroids_kernel<uint16_t>, grid, dim3(128), 0, stream, (const uint16_t*)x, idx, init_c,
+                           c64, s->n, k, s->d);
+    else
+        hipLaunchKernelGGL(init_centroids_kernel<float>, grid, dim3(128), 0, stream, (const float*)x, idx, init_c, c64,
+                           s->n, k, s->d);
+}
+
+extern "C" int svoo_cocluster(const svoo_shape* shape, const void* q, const void* k, const int32_t* init_q_idx,
+                              const int32_t* init_k_idx, const float* init_cq, const float* init_ck, int32_t iters,
+                              int32_t* labels_q, int32_t* labels_k, float* cq, float* ck, int32_t* counts_q,
+                              int32_t* counts_k, double* objective, void* ws, size_t ws_bytes, void* hip_stream) {
+    int st = check_shape(shape, true);
+    if (st != SVOO_OK) return st;
+    if (!q || !k || !labels_q || !labels_k || !cq || !ck || !counts_q || !counts_k || !ws)
+        return SVOO_ERR_INVALID_ARG;
+    if ((!init_q_idx && !init_cq) || (!init_k_idx && !init_ck)) return SVOO_ERR_INVALID_ARG;
+    if (iters < 1 || iters > 1000) return SVOO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || (((uintptr_t)ws) & 255u) != 0) return SVOO_ERR_INVALID_ARG;
+    if (shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    const ClusterWs w = carve_cluster_ws(shape, ws);
+    if (ws_bytes < w.bytes) return SVOO_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    launch_init_centroids(shape, q, init_q_idx, init_cq, w.c64q, shape->kq, stream);
+    launch_init_centroids(shape, k, init_k_idx, init_ck, w.c64k, shape->kk, stream);
+    for (int it = 0; it < iters; ++it) {
+        const bool last = it == iters - 1;
+        // Step A: keys against query anchors (old C_q), own centroids old C_k.
+        st = assign_side(shape, w, k, w.c64k, shape->kk, w.c64q, shape->kq, labels_k, objective != nullptr, stream);
+        if (st != SVOO_OK) return st;
+        if (objective)
+            launch_objective(shape, w, k, shape->kk, labels_k, objective + (size_t)it * 2, iters * 2, stream);
+        st = sort_labels(shape->bh, shape->n, shape->kk, labels_k, w.perm, w.offsets, nullptr, w.chunk_hist, stream);
+        if (st != SVOO_OK) return st;
+        launch_centroid_update(shape, k, w.perm, w.offsets, w.c64k, last ? ck : nullptr, last ? counts_k : nullptr,
+                               shape->kk, stream);
+        // Step B: queries against the NEW key anchors, own centroids the OLD C_q.
+        st = assign_side(shape, w, q, w.c64q, shape->kq, w.c64k, shape->kk, labels_q, objective != nullptr, stream);
+        if (st != SVOO_OK) return st;
+        if (objective)
+            launch_objective(shape, w, q, shape->kq, labels_q, objective + (size_t)it * 2 + 1, iters * 2, stream);
+        st = sort_labels(shape->bh, shape->n, shape->kq, labels_q, w.perm, w.offsets, nullptr, w.chunk_hist, stream);
+        if (st != SVOO_OK) return st;
+        launch_centroid_update(shape, q, w.perm, w.offsets, w.c64q, last ? cq : nullptr, last ? counts_q : nullptr,
+                               shape->kq, stream);
+    }
+    return launch_status();
+}
+
+extern "C" int svoo_assign(const svoo_shape* shape, const void* x, const float* c_own, int32_t k_own,
+                           const float* c_opp, int32_t k_opp, int32_t* labels, void* ws, size_t ws_bytes,
+                           void* hip_stream) {
+    int st = check_shape(shape, false);
+    if (st != SVOO_OK) return st;
+    if (!x || !c_own || !c_opp || !labels || !ws) return SVOO_ERR_INVALID_ARG;
+    if (k_own < 1 || k_opp < 1 || k_own > SVOO_MAX_K || k_opp > SVOO_MAX_K) return SVOO_ERR_INVALID_ARG;
+    if (!aligned16(x) || (((uintptr_t)ws) & 255u) != 0 || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    svoo_shape s = *shape;
+    s.kq = k_own;  // carve with own side in the "q" slot, opp side in the "k" slot
+    s.kk = k_opp;
+    const ClusterWs w = carve_cluster_ws(&s, ws);
+    if (ws_bytes < w.bytes) return SVOO_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const size_t n_own = (size_t)s.bh * k_own * s.d, n_opp = (size_t)s.bh * k_opp * s.d;
+    hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n_own + 255) / 256), dim3(256), 0, stream, c_own, w.c64q, n_own);
+    hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n_opp + 255) / 256), dim3(256), 0, stream, c_opp, w.c64k, n_opp);
+    return assign_side(&s, w, x, w.c64q, k_own, w.c64k, k_opp, labels, false, stream);
+}

@@ -1,0 +1,75 @@
+// Shared host/device helpers of libsvoo (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "svoo.h"
+
+#define SVOO_MAX_K 1024
+#define SVOO_WAVE 64
+
+// ---------------------------------------------------------------------------------------------
+// bf16 <-> float (bit-level; bf16 is the upper half of an IEEE binary32)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side helpers
+// ---------------------------------------------------------------------------------------------
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+static inline int elem_size(int dtype) { return dtype == SVOO_BF16 ? 2 : 4; }
+
+// Shape checks shared by every entry point.  Returns SVOO_OK or the error to hand back.
+static inline int check_shape(const svoo_shape* s, bool need_clusters) {
+    if (!s) return SVOO_ERR_INVALID_ARG;
+    if (s->bh < 1 || s->n < 1 || s->n > (1 << 24)) return SVOO_ERR_INVALID_ARG;
+    if ((long long)s->bh * s->n > 0x7fffffffLL) return SVOO_ERR_INVALID_ARG;
+    if (s->dtype != SVOO_BF16 && s->dtype != SVOO_F32) return SVOO_ERR_UNSUPPORTED;
+    if (s->d != 64 && s->d != 128) return SVOO_ERR_UNSUPPORTED;
+    if (need_clusters) {
+        if (s->kq < 1 || s->kk < 1 || s->kq > SVOO_MAX_K || s->kk > SVOO_MAX_K) return SVOO_ERR_INVALID_ARG;
+        if (s->kq > s->n || s->kk > s->n) return SVOO_ERR_INVALID_ARG;
+    }
+    return SVOO_OK;
+}
+
+// Bump allocator over the caller's workspace; every block 256-byte aligned.
+struct WsCarver {
+    char* base;
+    size_t used;
+    explicit WsCarver(void* p) : base((char*)p), used(0) {}
+    template <typename T>
+    T* take(size_t count) {
+        T* r = (T*)(base + used);
+        used += align_up(count * sizeof(T), 256);
+        return r;
+    }
+};
+
+static inline int launch_status() { return hipGetLastError() == hipSuccess ? SVOO_OK : SVOO_ERR_HIP; }
+
+// ---------------------------------------------------------------------------------------------
+// internal entry points shared between translation units
+// ---------------------------------------------------------------------------------------------
+// Stable counting sort of labels [bh, n] into perm / offsets (and counts, nullable).
+// chunk_hist: scratch int32 [bh * sort_chunks(n) * n_clusters].
+size_t sort_scratch_ints(int bh, int n, int n_clusters);
+int sort_labels(int bh, int n, int n_clusters, const int32_t* labels, int32_t* perm, int32_t* offsets,
+                int32_t* counts, int32_t* chunk_hist, hipStream_t stream);

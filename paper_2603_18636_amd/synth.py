@@ -203,5 +203,5 @@ def make_layer(cfg: Config, layer: int = 0, heads: Optional[List[int]] = None,
     heads = list(range(cfg.heads)) if heads is None else list(heads)
     parts = [make_head(cfg, layer, h, **overrides) for h in heads]
     out = {key: np.stack([p[key] for p in parts], axis=0) for key in parts[0]}
-    out["keep"] = np.full(len(heads), layer_keeps(cfg)[layer], dtype=np.float32)
+    out["keep"] = np.full(len(heads), layer_keeps(cfg)[layer % cfg.n_layers], dtype=np.float32)
     return out

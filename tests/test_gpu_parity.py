@@ -1,0 +1,317 @@
+"""GPU parity: every step of the HIP path, called through the C boundary, against the fp64 oracle
+on the same seeded inputs.  Integer outputs (labels, permutations, offsets, masks) bit-exact
+(near-ties below 1e-6 relative are counted and allowed); attention within the stated tolerance."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import svoo_oracle as so
+from paper_2603_18636_amd import svoo, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def small_cfg1_head(layer=0, head=0, grid=(6, 12, 20), n_seeds=24, kq=24, kk=20, d=128, dtype="bf16"):
+    """Config-1 generator shrunk to N=1440 (several 128-row tiles, ragged tails everywhere)."""
+    return synth.make_head(synth.CONFIGS[1], layer, head, grid=grid, n_seeds=n_seeds, kq=kq, kk=kk, d=d, dtype=dtype)
+
+
+# ------------------------------------------------------------------------------------------ permute
+@pytest.mark.parametrize("n,k", [(1, 1), (63, 3), (64, 1), (65, 7), (511, 16), (512, 16), (513, 300), (5000, 1024),
+                                  (4097, 256)])
+def test_sort_perm_offsets_bit_exact(n, k):
+    rng = np.random.default_rng(n * 1000 + k)
+    bh = 3
+    labels = rng.integers(0, k, size=(bh, n)).astype(np.int32)
+    if k > 4:
+        labels[labels == 2] = 3          # an empty cluster in the middle
+        labels[labels == k - 1] = 0      # and at the end
+    perm, offsets, _ = svoo.permute(H.to_dev(labels), k, [])
+    perm, offsets = H.to_np(perm), H.to_np(offsets)
+    for b in range(bh):
+        p_ref, o_ref = so.stable_permutation(labels[b], k)
+        assert (perm[b] == p_ref).all()
+        assert (offsets[b] == o_ref).all()
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_permute_unpermute_rows(dtype, d):
+    rng = np.random.default_rng(7)
+    bh, n, k = 2, 3001, 37
+    labels = rng.integers(0, k, size=(bh, n)).astype(np.int32)
+    xs = [rng.standard_normal((bh, n, d)).astype(np.float32) for _ in range(3)]
+    if dtype == "bf16":
+        xs = [synth.round_to_bf16(x) for x in xs]
+    dev = [H.to_dev(x, dtype) for x in xs]
+    perm, offsets, outs = svoo.permute(H.to_dev(labels), k, dev)
+    perm_np = H.to_np(perm)
+    for x, o in zip(xs, outs):
+        o = H.to_np(o)
+        for b in range(bh):
+            assert (o[b] == x[b][perm_np[b]]).all()
+    back = svoo.unpermute(outs[1], perm)
+    assert (H.to_np(back) == xs[1]).all()
+
+
+# ------------------------------------------------------------------------------------------ assign
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_assign_matches_oracle_teacher_forced(dtype, d):
+    h = small_cfg1_head(d=d, dtype=dtype)
+    q, k = h["q"], h["k"]
+    cq = q[h["init_q_idx"]].astype(np.float32)
+    ck = k[h["init_k_idx"]].astype(np.float32)
+    # Step A shape: keys against own centroids ck through anchors cq
+    ref, best, second = H.oracle_assign(k, ck, cq)
+    got = svoo.assign(H.to_dev(k[None], dtype), H.to_dev(ck[None]), H.to_dev(cq[None]))
+    H.compare_labels(H.to_np(got)[0], ref, best, second)
+    # centroids that are means (not bf16-exact), taken from the oracle's first half-step
+    cc = so.cocluster(q, k, h["init_q_idx"], h["init_k_idx"], 1)
+    ck1 = cc["ck"].astype(np.float32)
+    cq0 = cq
+    ref, best, second = H.oracle_assign(q, cq0, ck1)
+    got = svoo.assign(H.to_dev(q[None], dtype), H.to_dev(cq0[None]), H.to_dev(ck1[None]))
+    H.compare_labels(H.to_np(got)[0], ref, best, second)
+
+
+def test_assign_degenerate_anchor_and_zero_tokens():
+    """An all-zero own-side centroid has a zero affinity row (below the Norm floor); zero tokens have
+    a zero affinity vector.  The general form of the distance must still match the oracle."""
+    h = small_cfg1_head(dtype="f32", d=64)
+    k = h["k"].copy()
+    q = h["q"]
+    k[10] = 0.0
+    k[500:520] = 0.0
+    ck = k[h["init_k_idx"]].astype(np.float32)
+    ck[3] = 0.0
+    cq = q[h["init_q_idx"]].astype(np.float32)
+    ref, best, second = H.oracle_assign(k, ck, cq)
+    got = H.to_np(svoo.assign(H.to_dev(k[None], "f32"), H.to_dev(ck[None]), H.to_dev(cq[None])))[0]
+    # zero tokens sit at distance b_j from every anchor: degenerate anchor 3 (b = 0) must win
+    assert (ref[500:520] == 3).all() and ref[10] == 3
+    H.compare_labels(got, ref, best, second)
+
+
+# ------------------------------------------------------------------------------------------ cocluster
+def run_cocluster_case(h, iters, dtype, want_objective=False):
+    q, k = h["q"], h["k"]
+    out = svoo.cocluster(H.to_dev(q[None], dtype), H.to_dev(k[None], dtype), H.to_dev(h["init_q_idx"][None]),
+                         H.to_dev(h["init_k_idx"][None]), iters, want_objective=want_objective)
+    ref = so.cocluster(q, k, h["init_q_idx"], h["init_k_idx"], iters)
+    return out, ref
+
+
+@pytest.mark.parametrize("dtype,d,iters", [("bf16", 128, 3), ("f32", 64, 5), ("bf16", 64, 2)])
+def test_cocluster_matches_oracle(dtype, d, iters):
+    h = small_cfg1_head(d=d, dtype=dtype)
+    out, ref = run_cocluster_case(h, iters, dtype, want_objective=True)
+    last_k = [t for t in ref["trace"] if t["side"] == "k"][-1]
+    last_q = [t for t in ref["trace"] if t["side"] == "q"][-1]
+    near = H.compare_labels(H.to_np(out["labels_k"])[0], ref["labels_k"], last_k["best"], last_k["second"])
+    near += H.compare_labels(H.to_np(out["labels_q"])[0], ref["labels_q"], last_q["best"], last_q["second"])
+    if near == 0:
+        assert (H.to_np(out["counts_q"])[0] == ref["counts_q"]).all()
+        assert (H.to_np(out["counts_k"])[0] == ref["counts_k"]).all()
+        np.testing.assert_array_equal(H.to_np(out["cq"])[0], ref["cq"].astype(np.float32))
+        np.testing.assert_array_equal(H.to_np(out["ck"])[0], ref["ck"].astype(np.float32))
+        obj = H.to_np(out["objective"])[0]
+        j_ref = np.array([t["J"] for t in ref["trace"]]).reshape(iters, 2)
+        np.testing.assert_allclose(obj, j_ref, rtol=1e-9)
+
+
+def test_cocluster_config0_full():
+    cfg = synth.CONFIGS[0]
+    h = synth.make_head(cfg, 0, 0)
+    out, ref = run_cocluster_case(h, cfg.iters, "f32")
+    assert (H.to_np(out["labels_q"])[0] == ref["labels_q"]).all()
+    assert (H.to_np(out["labels_k"])[0] == ref["labels_k"]).all()
+    np.testing.assert_array_equal(H.to_np(out["cq"])[0], ref["cq"].astype(np.float32))
+
+
+def test_cocluster_warm_start_and_empty_clusters():
+    """Warm start from given centroids; duplicated centroids leave clusters empty (ties go to the
+    lowest index), and an empty cluster keeps its previous centroid."""
+    h = small_cfg1_head(dtype="bf16")
+    q, k = h["q"], h["k"]
+    cq0 = q[h["init_q_idx"]].astype(np.float32)
+    ck0 = k[h["init_k_idx"]].astype(np.float32)
+    ck0[5] = ck0[2]
+    ck0[7] = ck0[2]
+    cq0[1] = cq0[0]
+    out = svoo.cocluster(H.to_dev(q[None], "bf16"), H.to_dev(k[None], "bf16"), iters=2, init_cq=H.to_dev(cq0[None]),
+                         init_ck=H.to_dev(ck0[None]))
+    ref = so.cocluster(q, k, None, None, 2, init_cq=cq0, init_ck=ck0)
+    assert (H.to_np(out["labels_k"])[0] == ref["labels_k"]).all()
+    assert (H.to_np(out["labels_q"])[0] == ref["labels_q"]).all()
+    counts_k = H.to_np(out["counts_k"])[0]
+    assert (counts_k == ref["counts_k"]).all()
+    np.testing.assert_array_equal(H.to_np(out["ck"])[0], ref["ck"].astype(np.float32))
+
+
+# ------------------------------------------------------------------------------------------ block mask
+MODES = {"budget": (1.0, 0.0), "paper": (0.95, 0.1), "top_p": (None, 0.1)}
+
+
+@pytest.mark.parametrize("mode", ["budget", "paper", "top_p"])
+@pytest.mark.parametrize("kq,kk,d", [(24, 20, 128), (16, 300, 64), (5, 1024, 128)])
+def test_block_mask_bit_exact(mode, kq, kk, d):
+    rng = np.random.default_rng(kq * 7 + kk)
+    bh = 3
+    cq = (rng.standard_normal((bh, kq, d)) * 1.5).astype(np.float32)
+    ck = (rng.standard_normal((bh, kk, d)) * 1.5).astype(np.float32)
+    nq = rng.integers(0, 50, size=(bh, kq)).astype(np.int32)
+    nk = rng.integers(0, 50, size=(bh, kk)).astype(np.int32)
+    nq[:, 0] = 0
+    nk[:, 1] = 0
+    nk[2, :] = 0
+    nk[2, 3] = 9            # a slice with a single non-empty key block
+    keep = np.array([0.2, 0.07, 0.5], dtype=np.float32)
+    tau, theta = MODES[mode]
+    if tau is None:
+        tau, keep = 0.6, np.ones(bh, dtype=np.float32)
+    tau32, theta32, scale = float(np.float32(tau)), float(np.float32(theta)), H.scale_of(d)
+    cnt, lst, bitmap = svoo.block_mask(H.to_dev(cq), H.to_dev(ck), H.to_dev(nq), H.to_dev(nk), H.to_dev(keep), tau32,
+                                       theta32, scale)
+    cnt, lst, bitmap = H.to_np(cnt), H.to_np(lst), H.to_np(bitmap)
+    for b in range(bh):
+        ref = so.block_mask(cq[b], ck[b], nq[b], nk[b], keep[b], tau32, theta32, scale)
+        margins = so.selection_margins(cq[b], ck[b], nq[b], nk[b], keep[b], tau32, theta32, scale)
+        for r in range(kq):
+            if margins[r] < H.NEAR_TIE:
+                continue
+            assert (bitmap[b, r].astype(bool) == ref[r]).all(), (b, r)
+            assert cnt[b, r] == ref[r].sum()
+            assert (lst[b, r, :cnt[b, r]] == np.nonzero(ref[r])[0]).all()
+            assert (lst[b, r, cnt[b, r]:] == -1).all()
+
+
+# ------------------------------------------------------------------------------------------ attention
+@pytest.mark.parametrize("dtype,d,n", [("bf16", 128, 1000), ("bf16", 64, 333), ("f32", 64, 700), ("f32", 128, 129),
+                                       ("bf16", 128, 64), ("bf16", 128, 1)])
+def test_dense_attn_matches_oracle(dtype, d, n):
+    rng = np.random.default_rng(n + d)
+    bh = 2
+    q, k, v = (rng.standard_normal((bh, n, d)).astype(np.float32) for _ in range(3))
+    q *= 1.7
+    if dtype == "bf16":
+        q, k, v = (synth.round_to_bf16(x) for x in (q, k, v))
+    scale = H.scale_of(d)
+    out, lse = svoo.attn(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), scale, want_lse=True)
+    out, lse = H.to_np(out), H.to_np(lse)
+    for b in range(bh):
+        ref = so.dense_attention(q[b], k[b], v[b], scale)
+        H.assert_attn_close(out[b], ref, dtype, f"dense b={b}")
+        s = scale * (q[b].astype(np.float64) @ k[b].astype(np.float64).T)
+        lse_ref = np.log(np.exp(s - s.max(1, keepdims=True)).sum(1)) + s.max(1)
+        np.testing.assert_allclose(lse[b], lse_ref, atol=2e-2 if dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_sparse_attn_matches_oracle_random_mask(dtype, d):
+    """Random labels (ragged cluster sizes, some empty) and a random mask: pins the key-stream walk,
+    tile tails, row tails and the masked softmax independently of the clustering."""
+    h = small_cfg1_head(dtype=dtype, d=d)
+    q, k, v = h["q"], h["k"], h["v"]
+    n = q.shape[0]
+    kq, kk = 9, 13
+    rng = np.random.default_rng(d)
+    lq = rng.choice(kq, size=n, p=np.array([30, 1, 0, 8, 5, 0, 20, 3, 2]) / 69).astype(np.int32)
+    lk = rng.choice(kk, size=n, p=np.array([1, 40, 0, 3, 3, 7, 0, 2, 9, 1, 1, 1, 5]) / 73).astype(np.int32)
+    mask = rng.random((kq, kk)) < 0.4
+    mask[np.arange(kq), rng.integers(0, kk, kq)] = True
+    nk = np.bincount(lk, minlength=kk)
+    mask[:, nk == 0] = False
+    mask[6, :] = nk > 0                      # one query block attends to everything
+    scale = H.scale_of(d)
+    qd, kd, vd = (H.to_dev(x[None], dtype) for x in (q, k, v))
+    perm_q, q_off, (qs,) = svoo.permute(H.to_dev(lq[None]), kq, [qd])
+    perm_k, k_off, (ks, vs) = svoo.permute(H.to_dev(lk[None]), kk, [kd, vd])
+    cnt = mask.sum(1).astype(np.int32)
+    lst = np.full((kq, kk), -1, dtype=np.int32)
+    for r in range(kq):
+        lst[r, :cnt[r]] = np.nonzero(mask[r])[0]
+    o_sorted = svoo.block_sparse_attn(qs, ks, vs, q_off, k_off, H.to_dev(cnt[None]), H.to_dev(lst[None]), scale)
+    out = H.to_np(svoo.unpermute(o_sorted, perm_q))[0]
+    ref = so.sparse_attention(q, k, v, lq, lk, mask, scale)
+    H.assert_attn_close(out, ref, dtype, "sparse random mask")
+
+
+def test_sparse_attn_no_kept_block_writes_zeros():
+    h = small_cfg1_head(dtype="bf16")
+    n = h["q"].shape[0]
+    lq = (np.arange(n) % 3).astype(np.int32)
+    lk = (np.arange(n) % 2).astype(np.int32)
+    qd, kd, vd = (H.to_dev(h[x][None], "bf16") for x in "qkv")
+    perm_q, q_off, (qs,) = svoo.permute(H.to_dev(lq[None]), 3, [qd])
+    perm_k, k_off, (ks, vs) = svoo.permute(H.to_dev(lk[None]), 2, [kd, vd])
+    cnt = np.array([[1, 0, 2]], dtype=np.int32)
+    lst = np.array([[[1, -1], [-1, -1], [0, 1]]], dtype=np.int32)
+    o = H.to_np(svoo.unpermute(svoo.block_sparse_attn(qs, ks, vs, q_off, k_off, H.to_dev(cnt), H.to_dev(lst), 0.088),
+                               perm_q))[0]
+    assert (o[lq == 1] == 0).all()
+    mask = np.array([[False, True], [False, False], [True, True]])
+    ref = so.sparse_attention(h["q"], h["k"], h["v"], lq, lk, mask, float(np.float32(0.088)))
+    H.assert_attn_close(o, ref, "bf16", "no kept block")
+
+
+# ------------------------------------------------------------------------------------------ whole layer
+def run_layer_gpu(data, dtype, kq, kk, iters, keep, tau, theta):
+    bh, n, d = data["q"].shape
+    layer = svoo.Layer(bh, n, d, H.torch_dtype(dtype), kq, kk, H.DEV)
+    qd, kd, vd = (H.to_dev(data[x], dtype) for x in "qkv")
+    out = layer.run(qd, kd, vd, H.to_dev(data["init_q_idx"]), H.to_dev(data["init_k_idx"]), iters,
+                    H.to_dev(np.full(bh, keep, dtype=np.float32)), float(np.float32(tau)), float(np.float32(theta)))
+    torch.cuda.synchronize()
+    return layer, out
+
+
+@pytest.mark.parametrize("mode", ["budget", "paper"])
+def test_layer_config0_end_to_end(mode):
+    cfg = synth.CONFIGS[0]
+    data = synth.make_layer(cfg, 0)
+    tau, theta = MODES[mode]
+    tau32, theta32 = float(np.float32(tau)), float(np.float32(theta))
+    layer, out = run_layer_gpu(data, "f32", cfg.kq, cfg.kk, cfg.iters, cfg.keep, tau, theta)
+    ref = so.layer(data["q"][0], data["k"][0], data["v"][0], data["init_q_idx"][0], data["init_k_idx"][0], cfg.iters,
+                   np.float32(cfg.keep), tau32, theta32, scale=H.scale_of(cfg.d))
+    assert (H.to_np(layer.labels_q)[0] == ref["labels_q"]).all()
+    assert (H.to_np(layer.labels_k)[0] == ref["labels_k"]).all()
+    p_ref, o_ref = so.stable_permutation(ref["labels_q"], cfg.kq)
+    assert (H.to_np(layer.perm_q)[0] == p_ref).all() and (H.to_np(layer.q_offsets)[0] == o_ref).all()
+    assert (H.to_np(layer.bitmap)[0].astype(bool) == ref["mask"]).all()
+    H.assert_attn_close(H.to_np(out)[0], ref["out"], "f32", "config0 layer")
+
+
+def test_layer_small_config1_end_to_end_and_keep1_is_dense():
+    cfg = synth.CONFIGS[1]
+    grid, kq, kk = (6, 12, 20), 24, 20
+    data = synth.make_layer(cfg, 0, heads=[0, 1, 2], grid=grid, n_seeds=24, kq=kq, kk=kk)
+    layer, out = run_layer_gpu(data, "bf16", kq, kk, cfg.iters, cfg.keep, 1.0, 0.0)
+    out = H.to_np(out)
+    scale = H.scale_of(cfg.d)
+    for b in range(3):
+        ref = so.layer(data["q"][b], data["k"][b], data["v"][b], data["init_q_idx"][b], data["init_k_idx"][b],
+                       cfg.iters, np.float32(cfg.keep), 1.0, 0.0, scale=scale)
+        assert (H.to_np(layer.labels_q)[b] == ref["labels_q"]).all()
+        assert (H.to_np(layer.labels_k)[b] == ref["labels_k"]).all()
+        assert (H.to_np(layer.bitmap)[b].astype(bool) == ref["mask"]).all()
+        H.assert_attn_close(out[b], ref["out"], "bf16", f"small config1 b={b}")
+    # keep = 1: the sparse path must reproduce dense attention
+    layer1, out1 = run_layer_gpu(data, "bf16", kq, kk, cfg.iters, 1.0, 1.0, 0.1)
+    out1 = H.to_np(out1)
+    for b in range(3):
+        ref = so.dense_attention(data["q"][b], data["k"][b], data["v"][b], scale)
+        H.assert_attn_close(out1[b], ref, "bf16", f"keep=1 b={b}")
+
+
+def test_layer_is_deterministic():
+    cfg = synth.CONFIGS[1]
+    data = synth.make_layer(cfg, 1, heads=[0, 1], grid=(6, 12, 20), n_seeds=24, kq=24, kk=20)
+    l1, o1 = run_layer_gpu(data, "bf16", 24, 20, 3, 0.2, 0.95, 0.1)
+    o1 = o1.clone()
+    labels1 = l1.labels_q.clone()
+    l2, o2 = run_layer_gpu(data, "bf16", 24, 20, 3, 0.2, 0.95, 0.1)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    assert torch.equal(labels1, l2.labels_q)

@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the SVOO online stage on one MI355X.
+
+A step = one attention layer of the headline workload (benchmark configs[2]: 12 heads x 75,600
+tokens, d = 128, bf16, 256 + 256 clusters, 3 co-clustering iterations, per-layer keep ratio drawn
+from [0.08, 0.45]) through the whole hot path: svoo_cocluster -> svoo_permute (Q; K and V) ->
+svoo_block_mask -> svoo_block_sparse_attn -> svoo_unpermute, inputs already resident in HBM.
+Prints ONE JSON line: whole-layer kept-block TFLOP/s (`value`), ms per layer, the per-call
+breakdown, the dense svoo_attn time at the same shape, the roofline fraction of the block-sparse
+attention kernel, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+STEP_NAMES = ("cocluster", "permute", "block_mask", "sparse_attn", "unpermute")
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=12)
+    p.add_argument("--warmup", type=int, default=2)
+    p.add_argument("--config", type=int, default=2, help="workload id (BASELINE.json configs index)")
+    p.add_argument("--inputs", type=int, default=3, help="distinct resident layer inputs cycled through")
+    p.add_argument("--mode", default="budget", choices=["budget", "paper"],
+                   help="budget: keep ratio alone sets the number of kept blocks (tau=1, theta=0); "
+                        "paper: recall 0.95 with switch threshold 0.1")
+    p.add_argument("--keep", type=float, default=None, help="fixed keep ratio instead of the per-layer draw")
+    p.add_argument("--dense-reps", type=int, default=2)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--gen-workers", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
+    return p.parse_args()
+
+
+def cpu_baseline(cfg, data, keep, tau, theta, scale, kept_flops_layer):
+    """The fp64 oracle, as it stands, on a bounded sample: head 0 of the first resident layer, ONE
+    co-clustering iteration (both half-steps at full N), the block mask, and block-sparse attention
+    for 2048 evenly spaced query rows.  Scaled to a whole layer (x iterations, x N/2048 rows,
+    x heads) and expressed in the metric's unit."""
+    from oracle import svoo_oracle as so
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([int(x.get("num_threads", 1)) for x in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    q, k, v = data["q"][0], data["k"][0], data["v"][0]
+    n = q.shape[0]
+    t0 = time.perf_counter()
+    cc = so.cocluster(q, k, data["init_q_idx"][0], data["init_k_idx"][0], 1)
+    t_iter = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    mask = so.block_mask(cc["cq"].astype(np.float32).astype(np.float64), cc["ck"].astype(np.float32).astype(np.float64),
+                         cc["counts_q"], cc["counts_k"], keep, tau, theta, scale)
+    t_mask = time.perf_counter() - t0
+    rows = np.linspace(0, n - 1, 2048).astype(np.int64)
+    t0 = time.perf_counter()
+    so.sparse_attention(q, k, v, cc["labels_q"], cc["labels_k"], mask, scale, rows=rows)
+    t_attn = time.perf_counter() - t0
+    per_head = cfg.iters * t_iter + t_mask + t_attn * (n / rows.size)
+    layer_s = per_head * cfg.heads
+    return {
+        "value": kept_flops_layer / layer_s / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": (f"head 0 of layer 0: 1 of {cfg.iters} co-clustering iterations at full N ({t_iter:.1f} s), "
+                   f"block mask ({t_mask:.2f} s), sparse attention for 2048 of {n} query rows ({t_attn:.1f} s); "
+                   f"extrapolated to {cfg.iters} iterations, all rows, {cfg.heads} heads = {layer_s:.0f} s/layer"),
+        "measured_s": t_iter + t_mask + t_attn, "extrapolated_layer_s": layer_s,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (heads are independent problems and would shard across "
+              f"GPUs with no collective); --gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_18636_amd import svoo, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    cfg = synth.CONFIGS[args.config]
+    dev = "cuda:0"
+    tdtype = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    scale = float(np.float32(1.0 / math.sqrt(cfg.d)))
+    tau, theta = (1.0, 0.0) if args.mode == "budget" else (float(np.float32(0.95)), float(np.float32(0.1)))
+    keeps = synth.layer_keeps(cfg) if args.keep is None else np.full(cfg.n_layers, args.keep, dtype=np.float32)
+
+    # ---- resident inputs
+    t_gen = time.perf_counter()
+    n_inputs = max(1, min(args.inputs, cfg.n_layers))
+    host, inputs = [], []
+    for layer in range(n_inputs):
+        data = synth.make_layer(cfg, layer, workers=args.gen_workers)
+        if layer == 0:
+            host.append(data)
+        inputs.append({key: torch.from_numpy(data[key]).to(dev).to(tdtype if key in "qkv" else torch.int32)
+                       for key in ("q", "k", "v", "init_q_idx", "init_k_idx")})
+        print(f"[bench] layer input {layer} resident ({time.perf_counter() - t_gen:.1f} s)", file=sys.stderr, flush=True)
+    keep_dev = [torch.full((cfg.heads,), float(kp), dtype=torch.float32, device=dev) for kp in keeps]
+    layer_obj = svoo.Layer(cfg.heads, cfg.n, cfg.d, tdtype, cfg.kq, cfg.kk, dev)
+
+    def one_step(i, events=None):
+        x = inputs[i % n_inputs]
+        kp = keep_dev[i % len(keep_dev)]
+        calls = (
+            lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
+            lambda: layer_obj.step_permute(x["q"], x["k"], x["v"]),
+            lambda: layer_obj.step_block_mask(kp, tau, theta, scale),
+            lambda: layer_obj.step_attn(scale),
+            lambda: layer_obj.step_unpermute(),
+        )
+        for c, call in enumerate(calls):
+            if events is not None:
+                events[c][0].record()
+            call()
+            if events is not None:
+                events[c][1].record()
+
+    for i in range(args.warmup):
+        one_step(i)
+        torch.cuda.synchronize()
+        print(f"[bench] warm-up step {i} done", file=sys.stderr, flush=True)
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in STEP_NAMES]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(i, ev[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    step_ms = np.array([[a.elapsed_time(b) for (a, b) in ev[i]] for i in range(args.steps)])
+    print(f"[bench] timed {args.steps} steps: {ms_per_step:.2f} ms/step", file=sys.stderr, flush=True)
+
+    # ---- kept-block work per step (untimed re-run of clustering + mask; results are deterministic)
+    kept_flops, phis = [], []
+    cache = {}
+    for i in range(args.steps):
+        key = (i % n_inputs, i % len(keep_dev))
+        if key not in cache:
+            x = inputs[key[0]]
+            layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters)
+            layer_obj.step_block_mask(keep_dev[key[1]], tau, theta, scale)
+            nq = layer_obj.counts_q.double()
+            nk = layer_obj.counts_k.double()
+            pairs = torch.einsum("bq,bqk,bk->", nq, layer_obj.bitmap.double(), nk).item()
+            cache[key] = pairs
+        pairs = cache[key]
+        kept_flops.append(4.0 * cfg.d * pairs)
+        phis.append(pairs / (cfg.heads * float(cfg.n) ** 2))
+    kept_flops = np.array(kept_flops)
+    total_kept = float(kept_flops.sum())
+
+    # ---- dense baseline of this build at the same shape
+    x = inputs[0]
+    layer_obj.dense(x["q"], x["k"], x["v"], scale)
+    torch.cuda.synchronize()
+    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    d0.record()
+    for _ in range(args.dense_reps):
+        layer_obj.dense(x["q"], x["k"], x["v"], scale)
+    d1.record()
+    torch.cuda.synchronize()
+    dense_ms = d0.elapsed_time(d1) / args.dense_reps
+    dense_flops = 4.0 * cfg.heads * float(cfg.n) ** 2 * cfg.d
+    print(f"[bench] dense svoo_attn: {dense_ms:.1f} ms", file=sys.stderr, flush=True)
+
+    attn_ms = step_ms[:, 3]
+    attn_tflops = float(kept_flops.sum() / (attn_ms.sum() * 1e-3) / 1e12)
+    value = total_kept / elapsed / 1e12
+    result = {
+        "metric": "kept-block TFLOPS & ms/layer (cluster+attn), 12h x 75600 tok d128 bf16",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.cfg_id}] {cfg.name}: {cfg.heads} heads x {cfg.n} tokens "
+                               f"(grid {cfg.grid}), d={cfg.d}, {cfg.dtype}, K_q={cfg.kq}, K_k={cfg.kk}, "
+                               f"{cfg.iters} co-clustering iterations, per-layer keep from the {cfg.n_layers}-layer "
+                               f"draw, selection mode {args.mode} (tau={tau}, theta={theta})",
+                   "global_batch": 1, "seq_len": cfg.n, "heads": cfg.heads, "resident_layer_inputs": n_inputs,
+                   "keep_mean": round(float(np.mean([keeps[i % len(keeps)] for i in range(args.steps)])), 4)},
+        "value_definition": "kept-block FLOPs (4*d*sum over kept blocks of n_r*n_j, true cluster sizes) of all "
+                            "timed steps / wall time of the whole layer path",
+        "kept_fraction_mean": round(float(np.mean(phis)), 4),
+        "breakdown_ms": {name: round(float(step_ms[:, c].mean()), 3) for c, name in enumerate(STEP_NAMES)},
+        "sparse_attn_kept_tflops": round(attn_tflops, 2),
+        "dense_attn_ms": round(dense_ms, 2), "dense_attn_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2),
+        "speedup_vs_own_dense": round(dense_ms / ms_per_step, 3),
+        "roofline": {"bound": "mfma", "kernel": "sparse_attn_bf16_kernel<128>", "achieved": round(attn_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": None,
+                     "launch_ms": round(float(attn_ms.mean()), 3),
+                     "flops_per_launch": float(kept_flops.mean())},
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
+        result["cpu_baseline"] = cpu_baseline(cfg, host[0], keeps[0], tau, theta, scale, float(kept_flops[0]))
+        result["cpu_baseline"]["value"] = round(result["cpu_baseline"]["value"], 6)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

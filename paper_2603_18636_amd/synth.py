@@ -73,10 +73,10 @@ CONFIGS: Dict[int, Config] = {
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
     """Round float32 values to the nearest bf16 (ties to even); result is float32."""
     x = np.ascontiguousarray(x, dtype=np.float32)
-    u = x.view(np.uint32).astype(np.uint64)
-    bias = ((u >> 16) & 1) + 0x7FFF
-    u = ((u + bias) >> 16) << 16
-    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+    u = x.view(np.uint32)
+    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    u = (u + bias) & np.uint32(0xFFFF0000)  # finite inputs well below the float32 maximum: no wrap-around
+    return u.view(np.float32).reshape(x.shape)
 
 
 def bf16_bits(x: np.ndarray) -> np.ndarray:
@@ -117,15 +117,18 @@ def voronoi_regions(u: np.ndarray, seeds: np.ndarray, weights: Optional[np.ndarr
     """
     n, s = u.shape[0], seeds.shape[0]
     out = np.empty(n, dtype=np.int64)
-    step = 8192
+    step = 16384
     denom = None
     if weights is not None:
         denom = (s * weights + 1e-9) ** (2.0 / 3.0)
     for a in range(0, n, step):
-        diff = u[a:a + step, None, :] - seeds[None, :, :]
-        d2 = np.einsum("nsc,nsc->ns", diff, diff)
+        ua = u[a:a + step]
+        d2 = np.zeros((ua.shape[0], s))
+        for c in range(3):
+            diff = ua[:, c:c + 1] - seeds[None, :, c]
+            d2 += diff * diff
         if denom is not None:
-            d2 = d2 / denom[None, :]
+            d2 /= denom[None, :]
         out[a:a + step] = np.argmin(d2, axis=1)
     return out
 
@@ -197,11 +200,17 @@ def make_head(cfg: Config, layer: int, head: int, grid: Optional[Tuple[int, int,
             "region": region.astype(np.int32)}
 
 
-def make_layer(cfg: Config, layer: int = 0, heads: Optional[List[int]] = None,
+def make_layer(cfg: Config, layer: int = 0, heads: Optional[List[int]] = None, workers: int = 1,
                **overrides) -> Dict[str, np.ndarray]:
-    """Stack ``make_head`` over heads: q/k/v [BH, N, d] float32, init_*_idx [BH, K] int32."""
+    """Stack ``make_head`` over heads: q/k/v [BH, N, d] float32, init_*_idx [BH, K] int32.
+    ``workers`` > 1 draws the heads in a thread pool (every head has its own generator state)."""
     heads = list(range(cfg.heads)) if heads is None else list(heads)
-    parts = [make_head(cfg, layer, h, **overrides) for h in heads]
+    if workers > 1 and len(heads) > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            parts = list(pool.map(lambda h: make_head(cfg, layer, h, **overrides), heads))
+    else:
+        parts = [make_head(cfg, layer, h, **overrides) for h in heads]
     out = {key: np.stack([p[key] for p in parts], axis=0) for key in parts[0]}
     out["keep"] = np.full(len(heads), layer_keeps(cfg)[layer % cfg.n_layers], dtype=np.float32)
     return out

@@ -155,6 +155,7 @@ int svoo_block_mask(const svoo_shape* shape, const float* cq, const float* ck,
  * in cluster order; q_offsets [bh, kq+1], k_offsets [bh, kk+1] from svoo_permute; block_count /
  * block_list from svoo_block_mask.  lse (nullable) [bh, n] float32: log-sum-exp of the scaled
  * logits over the kept keys (natural log).  A query block with no kept key writes zeros.
+ * scale must be finite and > 0.
  * bf16: both contractions on bf16 matrix cores with float32 accumulation, probabilities rounded to
  * bf16 before the second one; f32: float32 arithmetic throughout.
  */

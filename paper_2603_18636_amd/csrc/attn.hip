@@ -171,33 +171,100 @@ __device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_
 
 // ---------------------------------------------------------------------------------------------
 // bf16 matrix-core kernel, head dimension D (64 or 128), BM = 128 query rows per workgroup
+//
+// LDS: K and V tiles of 64 keys, row-major [key][D], double buffered, filled by direct
+// global->LDS 16-byte loads (no register staging).  A wave-load writes 1 KB = lane-consecutive
+// 16-byte slots, so the 16-byte chunk c of tile row r is fetched by the lane whose slot is
+// c ^ (r mod chunks-per-row): an XOR swizzle that makes both kinds of reads below conflict-free.
+//   K operand: ds_read_b128, lane (j, h) reads row 32 kb + j, chunk 2 c + h.
+//   V operand: ds_read_b64_tr_b16 (transposing read): within a 16-lane block the lane s points at
+//              4 consecutive d-columns of key row (s / 4); the lane i receives, for d-column i of
+//              the block, the 4 keys -- exactly the layout of the MFMA A operand of V^T.
+// The S^T accumulator of lane (j, h) holds, for query j, the keys 32 kb + 8 (v/4) + 4 h + v%4,
+// so 8 consecutive accumulators (v = 8t .. 8t+7) are two runs of 4 consecutive keys, which is
+// what two transposing reads deliver.
 // ---------------------------------------------------------------------------------------------
 #define BM_BF16 128
+#define RESCALE_LOG2 8.0f   // the running max is only raised when it is exceeded by 2^8
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
+    f32x2 x = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+}
 
 template <int D>
-__global__ void __launch_bounds__(ATT_THREADS)
+struct AttnLds {
+    static constexpr int ROWB = D * 2;            // bytes per K/V row
+    static constexpr int TILE = KT * ROWB;        // bytes per tile
+    static constexpr int SEG_BYTES = (2 * SVOO_MAX_K + 8) * 4;
+    static constexpr int BYTES = SEG_BYTES + 4 * TILE;   // seg tables + 2 x (K tile + V tile)
+};
+
+template <int D>
+__global__ void __launch_bounds__(ATT_THREADS, 2)
 sparse_attn_bf16_kernel(AttnArgs a) {
     constexpr int DC = D / 16;        // 16-wide contraction chunks of QK^T
     constexpr int DB = D / 32;        // 32-row blocks of O^T
-    constexpr int KPITCH = D * 2 + 16;
-    __shared__ int32_t seg_start[SVOO_MAX_K];
-    __shared__ int32_t seg_cum[SVOO_MAX_K + 1];
-    __shared__ int32_t scan[ATT_THREADS];
-    __shared__ int32_t rowidx[KT];
-    __shared__ __attribute__((aligned(16))) unsigned char k_lds[KT * KPITCH];
-    __shared__ __attribute__((aligned(16))) unsigned char vt_lds[D * VT_PITCH];
+    constexpr int CPR = D / 8;        // 16-byte chunks per row
+    constexpr int ROWB = AttnLds<D>::ROWB;
+    constexpr int TILE = AttnLds<D>::TILE;
+    constexpr int RPL = 64 / CPR;     // tile rows covered by one wave-load (1 KB)
+    constexpr int LPW = 16 / RPL;     // wave-loads per wave per tile (each wave owns 16 tile rows)
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    unsigned char* k_lds = smem;                  // [2][TILE]
+    unsigned char* v_lds = smem + 2 * TILE;       // [2][TILE]
+    int32_t* seg_start = (int32_t*)(smem + 4 * TILE);
+    int32_t* seg_cum = seg_start + SVOO_MAX_K;
+    int32_t* scan = (int32_t*)smem;               // setup scratch, aliases the K tiles
 
     TileInfo ti;
     if (!setup_tile(a, BM_BF16, seg_start, seg_cum, scan, ti)) return;
     const int b = blockIdx.y, tid = threadIdx.x;
     const int wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
     const uint16_t* qg = (const uint16_t*)a.q + (size_t)b * a.n * D;
-    const uint16_t* kg = (const uint16_t*)a.k + (size_t)b * a.n * D;
-    const uint16_t* vg = (const uint16_t*)a.v + (size_t)b * a.n * D;
+    const unsigned char* kg = (const unsigned char*)a.k + (size_t)b * a.n * ROWB;
+    const unsigned char* vg = (const unsigned char*)a.v + (size_t)b * a.n * ROWB;
+    const int total = ti.total;
+    const int n_tiles = (total + KT - 1) / KT;
 
-    // Q fragments: query row (wave, j), contraction elements 16c + 8h .. +7
+    // ---- key-stream walk: this lane tracks tile row 16*wave + lane%16 from tile to tile
+    int seg = 0, seg_end = 0, seg_delta = 0;
+    if (total > 0) {
+        seg_end = seg_cum[1];
+        seg_delta = seg_start[0] - seg_cum[0];
+    }
+    auto issue_tile = [&](int t, int buf) {
+        int p = t * KT + 16 * wave + (lane % 16);
+        p = p < total ? p : total - 1;        // rows past the end re-read the last key (masked later)
+        while (p >= seg_end) {                // terminates: p < total = seg_cum[n_seg]
+            ++seg;
+            seg_end = seg_cum[seg + 1];
+            seg_delta = seg_start[seg] - seg_cum[seg];
+        }
+        const int myrow = p + seg_delta;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int rl = i * RPL + lane / CPR;          // row within this wave's 16
+            const int row = __shfl(myrow, rl);
+            const int rho = 16 * wave + rl;                // tile row
+            const int chunk = (lane % CPR) ^ (rho % CPR);
+            const uint32_t goff = (uint32_t)row * ROWB + chunk * 16;
+            const int loff = buf * TILE + (16 * wave + i * RPL) * ROWB;
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kg + goff), (lds_ptr_t)(k_lds + loff), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vg + goff), (lds_ptr_t)(v_lds + loff), 16, 0, 0);
+        }
+    };
+
+    // ---- Q fragments: query row (wave, j), contraction elements 16c + 8h .. +7
     const int qrow = 32 * wave + j;
     const bool qvalid = qrow < ti.qn;
+    const bool wave_active = 32 * wave < ti.qn;
     bf16x8 qf[DC];
     {
         const uint4* src = (const uint4*)(qg + (size_t)(ti.q0 + (qvalid ? qrow : 0)) * D);
@@ -207,60 +274,42 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             qf[c] = __builtin_bit_cast(bf16x8, u);
         }
     }
+    // ---- per-lane LDS read offsets (bytes inside a tile; kb, t and buffer add constants)
+    int koff[DC];            // K: row j, chunk (2c + h) ^ (j % CPR)
+#pragma unroll
+    for (int c = 0; c < DC; ++c) koff[c] = j * ROWB + (((2 * c + h) ^ (j % CPR)) * 16);
+    int voff[2][DB];         // V: transposing read u of block db
+    {
+        const int s = lane % 16, blk = lane / 16;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const int rho = 8 * u + 4 * (blk / 2) + s / 4;            // + 32 kb + 16 t
+                const int chunk = 4 * db + 2 * (blk % 2) + (s % 4) / 2;
+                voff[u][db] = rho * ROWB + ((chunk ^ (rho % CPR)) * 16) + (s % 2) * 8;
+            }
+    }
+
     f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-    float m2 = -INFINITY;   // running max of the scaled logits, log2 domain
-    float lsum = 0.f;       // this lane's share of the running sum (its 16 keys of every 32)
     const float c2 = a.scale * LOG2E;
+    const float th_raw = RESCALE_LOG2 / c2;
+    float m_used = -INFINITY;   // reference max (raw logits) the probabilities are scaled by
+    float lsum = 0.f;           // this lane's share of the row sum
 
-    const int n_tiles = (ti.total + KT - 1) / KT;
+    if (n_tiles > 0) issue_tile(0, 0);
     for (int kt = 0; kt < n_tiles; ++kt) {
-        __syncthreads();  // previous tile fully consumed
-        if (tid < KT) {
-            const int p = kt * KT + tid;
-            rowidx[tid] = p < ti.total ? stream_row(seg_start, seg_cum, ti.n_seg, p) : -1;
-        }
-        __syncthreads();
-        // ---- stage K: 16 threads per row, 16 bytes each
-#pragma unroll
-        for (int it = 0; it < (KT * D * 2) / (ATT_THREADS * 16); ++it) {
-            constexpr int CPR = D / 8;  // 16-byte chunks per row
-            const int e = tid + it * ATT_THREADS;
-            const int row = e / CPR, chunk = e % CPR;
-            const int g = rowidx[row];
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (g >= 0) val = *(const uint4*)(kg + (size_t)g * D + chunk * 8);
-            const int key = row % 32, kb = row / 32;
-            const int mrow = 32 * kb + 8 * ((key % 16) / 4) + 4 * (key / 16) + (key % 4);
-            *(uint4*)(k_lds + mrow * KPITCH + chunk * 16) = val;
-        }
-        // ---- stage V transposed: unit = (pair of d columns, 4 consecutive keys)
-#pragma unroll
-        for (int it = 0; it < (KT / 4) * (D / 2) / ATT_THREADS; ++it) {
-            const int u = tid + it * ATT_THREADS;
-            const int wunit = u / 64;                 // wave-sized unit
-            const int dpl = lane % 16, kgl = lane / 16;
-            constexpr int DPB = D / 32;               // blocks of 16 d-pairs
-            const int dp = (wunit % DPB) * 16 + dpl;
-            const int kgrp = (wunit / DPB) * 4 + kgl;
-            uint32_t rr[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int g = rowidx[kgrp * 4 + e];
-                rr[e] = g >= 0 ? *(const uint32_t*)(vg + (size_t)g * D + 2 * dp) : 0u;
-            }
-            uint2 lo, hi;
-            lo.x = (rr[0] & 0xffffu) | (rr[1] << 16);
-            lo.y = (rr[2] & 0xffffu) | (rr[3] << 16);
-            hi.x = (rr[0] >> 16) | (rr[1] & 0xffff0000u);
-            hi.y = (rr[2] >> 16) | (rr[3] & 0xffff0000u);
-            *(uint2*)(vt_lds + (2 * dp) * VT_PITCH + kgrp * 8) = lo;
-            *(uint2*)(vt_lds + (2 * dp + 1) * VT_PITCH + kgrp * 8) = hi;
-        }
-        __syncthreads();
+        const int buf = kt & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();        // tile kt has landed for every wave; everyone is done with the other buffer
+        if (kt + 1 < n_tiles) issue_tile(kt + 1, buf ^ 1);
+        if (!wave_active) continue;
+        const unsigned char* kt_lds = k_lds + buf * TILE;
+        const unsigned char* vt_lds = v_lds + buf * TILE;
 
         // ---- S^T = K Q^T for the two 32-key blocks of the tile
         f32x16 s[2];
@@ -270,27 +319,40 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
 #pragma unroll
             for (int c = 0; c < DC; ++c) {
-                const uint4 u = *(const uint4*)(k_lds + (32 * kb + j) * KPITCH + c * 32 + h * 16);
+                const uint4 u = *(const uint4*)(kt_lds + kb * 32 * ROWB + koff[c]);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, u), qf[c], s[kb], 0, 0, 0);
             }
         }
-        // lane (j, h) now holds, for query j, keys 32*kb + 16*h + v  (v = accumulator index)
-        const int key_base = kt * KT + 16 * h;
-        float mx = -INFINITY;
+        // ragged last tile: keys past the end of the stream get -inf
+        if (kt == n_tiles - 1 && (total % KT) != 0) {
+            const int base = kt * KT + 4 * h;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (base + 32 * kb + 8 * (v / 4) + (v % 4) >= total) s[kb][v] = -INFINITY;
+        }
+        float mx = s[0][0];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float x = s[kb][v] * c2;
-                if (key_base + 32 * kb + v >= ti.total) x = -INFINITY;
-                s[kb][v] = x;
-                mx = fmaxf(mx, x);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m2, mx);
-        const float alpha = exp2f(m2 - m_new);   // m2 = -inf on the first tile gives 0
-        m2 = m_new;
-        lsum *= alpha;
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
+        {
+            const int mi = __float_as_int(mx);
+            auto r = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+            mx = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+        }
+        if (__any(mx > m_used + th_raw)) {
+            const float m_new = fmaxf(m_used, mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_used - m_new) * c2);   // 0 on the first tile
+            m_used = m_new;
+            lsum *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        }
+        const float mb = m_used * c2;
         bf16x8 pf[2][2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -299,17 +361,13 @@ sparse_attn_bf16_kernel(AttnArgs a) {
                 uint32_t w[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float p0 = exp2f(s[kb][8 * t + 2 * e] - m_new);
-                    const float p1 = exp2f(s[kb][8 * t + 2 * e + 1] - m_new);
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e], c2, -mb));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e + 1], c2, -mb));
                     lsum += p0 + p1;
-                    w[e] = pack_bf16x2(p0, p1);
+                    w[e] = pack2_bf16(p0, p1);
                 }
                 pf[kb][t] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
             }
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         // ---- O^T += V^T P^T
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -317,29 +375,55 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const uint4 u = *(const uint4*)(vt_lds + (32 * db + j) * VT_PITCH + (32 * kb + 16 * h + 8 * t) * 2);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, u), pf[kb][t], o[db], 0,
-                                                                    0, 0);
+                    const int cst = (32 * kb + 16 * t) * ROWB;
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[0][db]));
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                        (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[1][db]));
+                    const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], o[db], 0, 0, 0);
                 }
     }
 
-    // ---- epilogue: normalise and store.  Lane (j, h) holds O[q = j][d = 32 db + 8 (v/4) + 4 h + v%4].
-    const float ltot = lsum + __shfl_xor(lsum, 32);
-    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
-    if (qvalid) {
-        uint16_t* og = (uint16_t*)a.out + ((size_t)b * a.n + ti.q0 + qrow) * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint2 w;
-                w.x = pack_bf16x2(o[db][4 * g] * inv, o[db][4 * g + 1] * inv);
-                w.y = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-                *(uint2*)(og + 32 * db + 8 * g + 4 * h) = w;
-            }
-        if (a.lse && h == 0)
-            a.lse[(size_t)b * a.n + ti.q0 + qrow] = ltot > 0.f ? (m2 + log2f(ltot)) * 0.6931471805599453f : -INFINITY;
+    // ---- epilogue: normalise, transpose through LDS, store whole rows.
+    // Lane (j, h) holds O[q = j][d = 32 db + 8 (v/4) + 4 h + v%4].
+    float ltot;
+    {
+        const int li = __float_as_int(lsum);
+        auto r = __builtin_amdgcn_permlane32_swap(li, li, false, false);
+        ltot = __int_as_float(r[0]) + __int_as_float(r[1]);
     }
+    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    __syncthreads();   // all waves are done with the K/V tiles
+    unsigned char* stage = smem + wave * (32 * ROWB);      // 32 rows x ROWB per wave, inside the K buffers
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint2 w;
+            w.x = pack2_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv);
+            w.y = pack2_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+            const int chunk = 4 * db + g;                  // 16-byte chunk holding d = 32 db + 8 g ..
+            *(uint2*)(stage + j * ROWB + ((chunk ^ (j % CPR)) * 16) + 8 * h) = w;
+        }
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    {
+        unsigned char* og = (unsigned char*)a.out + ((size_t)b * a.n + ti.q0 + 32 * wave) * ROWB;
+        const int rows_here = ti.qn - 32 * wave;           // valid rows of this wave (may be <= 0)
+#pragma unroll
+        for (int i = 0; i < (32 * CPR) / 64; ++i) {
+            const int e = i * 64 + lane;
+            const int r = e / CPR, c = e % CPR;
+            if (r < rows_here) {
+                const uint4 val = *(const uint4*)(stage + r * ROWB + ((c ^ (r % CPR)) * 16));
+                *(uint4*)(og + (size_t)r * ROWB + c * 16) = val;
+            }
+        }
+    }
+    if (a.lse && qvalid && h == 0)
+        a.lse[(size_t)b * a.n + ti.q0 + qrow] =
+            ltot > 0.f ? (m_used * c2 + log2f(ltot)) * 0.6931471805599453f : -INFINITY;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -464,10 +548,18 @@ static int launch_sparse(const svoo_shape* s, AttnArgs& a, int32_t* tile_prefix,
     gx = (gx + 7) / 8 * 8;
     dim3 grid(gx, s->bh);
     if (s->dtype == SVOO_BF16) {
-        if (s->d == 128)
-            hipLaunchKernelGGL(sparse_attn_bf16_kernel<128>, grid, dim3(ATT_THREADS), 0, stream, a);
-        else
-            hipLaunchKernelGGL(sparse_attn_bf16_kernel<64>, grid, dim3(ATT_THREADS), 0, stream, a);
+        // more than 64 KB of dynamic LDS must be opted into per kernel
+        if (s->d == 128) {
+            if (hipFuncSetAttribute((const void*)sparse_attn_bf16_kernel<128>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, AttnLds<128>::BYTES) != hipSuccess)
+                return SVOO_ERR_HIP;
+            hipLaunchKernelGGL(sparse_attn_bf16_kernel<128>, grid, dim3(ATT_THREADS), AttnLds<128>::BYTES, stream, a);
+        } else {
+            if (hipFuncSetAttribute((const void*)sparse_attn_bf16_kernel<64>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, AttnLds<64>::BYTES) != hipSuccess)
+                return SVOO_ERR_HIP;
+            hipLaunchKernelGGL(sparse_attn_bf16_kernel<64>, grid, dim3(ATT_THREADS), AttnLds<64>::BYTES, stream, a);
+        }
     } else {
         if (s->d == 128)
             hipLaunchKernelGGL(sparse_attn_f32_kernel<128>, grid, dim3(ATT_THREADS), 0, stream, a);
@@ -489,7 +581,7 @@ extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sor
     if (!aligned16(q_sorted) || !aligned16(k_sorted) || !aligned16(v_sorted) || !aligned16(out_sorted) ||
         (((uintptr_t)ws) & 255u) != 0)
         return SVOO_ERR_INVALID_ARG;
-    if (!(scale == scale) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    if (!(scale > 0.0f) || !(scale < 1e30f) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
     if (ws_bytes < attn_ws_bytes(shape)) return SVOO_ERR_WORKSPACE_TOO_SMALL;
     AttnArgs a = {q_sorted, k_sorted, v_sorted, out_sorted, lse, q_offsets, k_offsets, block_count, block_list,
                   nullptr, shape->n, shape->kq, shape->kk, scale};
@@ -503,7 +595,7 @@ extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, 
     if (!q || !k || !v || !out || !ws) return SVOO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (((uintptr_t)ws) & 255u) != 0)
         return SVOO_ERR_INVALID_ARG;
-    if (!(scale == scale) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    if (!(scale > 0.0f) || !(scale < 1e30f) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
     svoo_shape s = *shape;
     s.kq = 1;
     s.kk = 1;

@@ -321,6 +321,179 @@ static void dispatch_token_tile(const svoo_shape* s, const void* x, const double
 }
 
 // ---------------------------------------------------------------------------------------------
+// bf16 matrix-core pre-filter for the assignment (bf16 tokens only).
+//
+// W is split into two bf16 terms, W = W_hi + W_lo + r with |r| <= 2^-17 |W| element-wise; tokens
+// are exact in bf16, so  f_j = <x, W_hi_j> + <x, W_lo_j>  (fp32 accumulation on the matrix cores)
+// satisfies |f_j - <x, W_j>| <= eps ||x|| ||W_j|| with eps covering the split remainder and the
+// fp32 accumulation of 2 d products.  If best - second > 2 eps ||x|| max_j ||W_j|| the fast
+// argmax is the exact argmax; otherwise (and for every token of a slice with a degenerate
+// anchor) the token is queued and the float64 kernel decides.  Equal scores have gap 0 and are
+// therefore always decided by the float64 kernel, which breaks ties towards the lowest index.
+//
+// Tokens are the B operand (one token per lane column, loaded straight from global memory into
+// registers, 64 tokens per wave), W blocks of 32 centroids are the A operand, streamed through
+// LDS with direct global->LDS loads and an XOR swizzle, double buffered.  S^T layout: lane
+// (j, h) holds for token j the centroids 32 cb + 8 (v/4) + 4 h + v%4.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+#define FAST_EPS 3.1e-5f   // 2^-16 + 256 * 2^-24, twice the analytic bound for d <= 128
+
+template <int D>
+__global__ void __launch_bounds__(128)
+split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo,
+               int32_t* __restrict__ wmax_bits, int k_own) {
+    __shared__ double red[128];
+    const int b = blockIdx.y, j = blockIdx.x, t = threadIdx.x;
+    const size_t o = ((size_t)b * k_own + j) * D + t;
+    double v = 0.0;
+    if (t < D) {
+        v = w64[o];
+        const float hi = bf16_to_f32(f32_to_bf16((float)v));
+        const float lo = (float)(v - (double)hi);
+        whi[o] = f32_to_bf16((float)v);
+        wlo[o] = f32_to_bf16(lo);
+    }
+    red[t] = v * v;
+    __syncthreads();
+    for (int s = 64; s > 0; s >>= 1) {
+        if (t < s) red[t] += red[t + s];
+        __syncthreads();
+    }
+    if (t == 0) {
+        float nrm = (float)sqrt(red[0]);
+        nrm = nrm * 1.0000002f + 1e-37f;   // round up
+        if (!(nrm < 3.0e38f)) nrm = 3.0e38f;
+        atomicMax(&wmax_bits[b], __float_as_int(nrm));   // non-negative floats order like their bit patterns
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(256, 2)
+assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ whi, const uint16_t* __restrict__ wlo,
+                   const int32_t* __restrict__ wmax_bits, const int32_t* __restrict__ flags,
+                   int32_t* __restrict__ labels, int32_t* __restrict__ list, int32_t* __restrict__ list_count, int n,
+                   int k_own) {
+    constexpr int DC = D / 16, CPR = D / 8, ROWB = D * 2;
+    constexpr int HALF = 32 * ROWB;          // one 32-centroid block of W_hi (or W_lo)
+    constexpr int RPL = 64 / CPR;            // rows per wave-load
+    constexpr int LPW = (32 / RPL) / 4;      // wave-loads per wave for one half block
+    __shared__ __attribute__((aligned(1024))) unsigned char wl[2 * 2 * HALF];   // [buf][hi|lo][32][ROWB]
+    const int b = blockIdx.y, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
+    const int t0 = blockIdx.x * 256 + 64 * wave;
+    const unsigned char* whb = (const unsigned char*)whi + (size_t)b * k_own * ROWB;
+    const unsigned char* wlb = (const unsigned char*)wlo + (size_t)b * k_own * ROWB;
+    const int n_blocks = (k_own + 31) / 32;
+
+    auto issue_block = [&](int cb, int buf) {
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int rl = (wave * LPW + i) * RPL + lane / CPR;     // row of the block, 0..31
+            int row = 32 * cb + rl;
+            row = row < k_own ? row : k_own - 1;
+            const int chunk = (lane % CPR) ^ (rl % CPR);
+            const uint32_t goff = (uint32_t)row * ROWB + chunk * 16;
+            const int loff = buf * 2 * HALF + (wave * LPW + i) * RPL * ROWB;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(whb + goff),
+                                             (__attribute__((address_space(3))) void*)(wl + loff), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wlb + goff),
+                                             (__attribute__((address_space(3))) void*)(wl + loff + HALF), 16, 0, 0);
+        }
+    };
+    issue_block(0, 0);
+
+    // token fragments and squared norms
+    bf16x8_t xf[2][DC];
+    float xn2[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        const int tok = t0 + 32 * tb + j;
+        const bool valid = tok < n;
+        const uint4* src = (const uint4*)(x + ((size_t)b * n + (valid ? tok : 0)) * D);
+        float acc = 0.f;
+#pragma unroll
+        for (int c = 0; c < DC; ++c) {
+            const uint4 u = valid ? src[2 * c + h] : make_uint4(0, 0, 0, 0);
+            xf[tb][c] = __builtin_bit_cast(bf16x8_t, u);
+            const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = __uint_as_float(wds[e] << 16), hi = __uint_as_float(wds[e] & 0xffff0000u);
+                acc = fmaf(lo, lo, acc);
+                acc = fmaf(hi, hi, acc);
+            }
+        }
+        const int ai = __float_as_int(acc);
+        auto r = __builtin_amdgcn_permlane32_swap(ai, ai, false, false);
+        xn2[tb] = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
+    int koff[DC];
+#pragma unroll
+    for (int c = 0; c < DC; ++c) koff[c] = j * ROWB + (((2 * c + h) ^ (j % CPR)) * 16);
+
+    float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
+    int bidx[2] = {0, 0};
+    for (int cb = 0; cb < n_blocks; ++cb) {
+        const int buf = cb & 1;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (cb + 1 < n_blocks) issue_block(cb + 1, buf ^ 1);
+        const unsigned char* base = wl + buf * 2 * HALF;
+        f32x16_t acc[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tb][v] = 0.f;
+#pragma unroll
+        for (int c = 0; c < DC; ++c) {
+            const bf16x8_t ah = __builtin_bit_cast(bf16x8_t, *(const uint4*)(base + koff[c]));
+            const bf16x8_t al = __builtin_bit_cast(bf16x8_t, *(const uint4*)(base + HALF + koff[c]));
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, xf[tb][c], acc[tb], 0, 0, 0);
+                acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, xf[tb][c], acc[tb], 0, 0, 0);
+            }
+        }
+        const int cbase = 32 * cb + 4 * h;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int cl = cbase + 8 * (v / 4) + (v % 4);
+                const float val = cl < k_own ? acc[tb][v] : -INFINITY;
+                second[tb] = __builtin_amdgcn_fmed3f(best[tb], second[tb], val);
+                bidx[tb] = val > best[tb] ? cl : bidx[tb];
+                best[tb] = fmaxf(best[tb], val);
+            }
+    }
+    const float wmax = __int_as_float(wmax_bits[b]);
+    const bool degenerate = flags[b] != 0;
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        auto rb = __builtin_amdgcn_permlane32_swap(__float_as_int(best[tb]), __float_as_int(best[tb]), false, false);
+        auto rs = __builtin_amdgcn_permlane32_swap(__float_as_int(second[tb]), __float_as_int(second[tb]), false, false);
+        auto ri = __builtin_amdgcn_permlane32_swap(bidx[tb], bidx[tb], false, false);
+        // for lanes < 32: [0] is the own value, [1] the other half's
+        const float b0 = __int_as_float(rb[0]), b1 = __int_as_float(rb[1]);
+        const float s0 = __int_as_float(rs[0]), s1 = __int_as_float(rs[1]);
+        const float fb = fmaxf(b0, b1);
+        const float fs = fmaxf(fminf(b0, b1), fmaxf(s0, s1));
+        const int fi = b0 >= b1 ? (int)ri[0] : (int)ri[1];
+        const int tok = t0 + 32 * tb + j;
+        if (h == 0 && tok < n) {
+            const float margin = 2.0f * FAST_EPS * sqrtf(xn2[tb]) * wmax;
+            const bool sure = (fb - fs) > margin;          // false for NaN as well
+            labels[(size_t)b * n + tok] = fi;
+            if (degenerate || !sure) {
+                const int pos = atomicAdd(&list_count[b], 1);
+                list[(size_t)b * n + pos] = tok;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Centroid update: C[j] = mean of the member rows, float64 sums in a fixed order.
 // One workgroup per (cluster, slice); members are perm[offsets[j] .. offsets[j+1]) in ascending
 // token order.  256 threads = G row-groups of (D/2) lanes; lane l adds elements 2l, 2l+1 of the
@@ -452,7 +625,8 @@ objective_sum_kernel(const double* __restrict__ terms, double* __restrict__ out,
 // ---------------------------------------------------------------------------------------------
 struct ClusterWs {
     double *c64q, *c64k, *w64, *pbar, *gram, *bterm, *nx2, *terms;
-    int32_t *flags, *perm, *offsets, *chunk_hist;
+    uint16_t *whi, *wlo;
+    int32_t *flags, *wmax_bits, *list_count, *list, *perm, *offsets, *chunk_hist;
     size_t bytes;
 };
 
@@ -468,7 +642,12 @@ static ClusterWs carve_cluster_ws(const svoo_shape* s, void* ws) {
     w.bterm = c.take<double>(bh * kmax);
     w.nx2 = c.take<double>(bh * (size_t)s->n);
     w.terms = c.take<double>(bh * (size_t)s->n);
-    w.flags = c.take<int32_t>(bh);
+    w.whi = c.take<uint16_t>(bh * kmax * s->d);
+    w.wlo = c.take<uint16_t>(bh * kmax * s->d);
+    w.flags = c.take<int32_t>(3 * bh);      // flags | wmax_bits | list_count, cleared by one fill
+    w.wmax_bits = w.flags + bh;
+    w.list_count = w.flags + 2 * bh;
+    w.list = c.take<int32_t>(bh * (size_t)s->n);
     w.perm = c.take<int32_t>(bh * (size_t)s->n);
     w.offsets = c.take<int32_t>(bh * (kmax + 1));
     w.chunk_hist = c.take<int32_t>(sort_scratch_ints(s->bh, s->n, (int)kmax));
@@ -483,7 +662,8 @@ size_t cluster_ws_bytes(const svoo_shape* s) { return carve_cluster_ws(s, nullpt
 static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, const double* c_own, int k_own,
                        const double* c_opp, int k_opp, int32_t* labels, bool want_nx2, hipStream_t stream) {
     const int d = s->d, bh = s->bh;
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((bh + 255) / 256), dim3(256), 0, stream, w.flags, 0, (size_t)bh);
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((3 * bh + 255) / 256), dim3(256), 0, stream, w.flags, 0,
+                       (size_t)3 * bh);
     // Pbar[j, c] = <c_own_j, c_opp_c>
     GemmArgs g1 = {c_own, c_opp, w.pbar, k_own, k_opp, d, (long long)k_own * d, (long long)k_opp * d,
                    (long long)k_own * k_opp, d, 1, 1, d};
@@ -502,8 +682,26 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
     // objective wants it, so the launch sequence never depends on device-side flags.
     dispatch_token_tile<MODE_QUADFORM>(s, x, w.gram, d, nullptr, w.flags, nullptr, nullptr, nullptr, want_nx2 ? 1 : 0,
                                        nullptr, w.nx2, stream);
-    dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels, nullptr,
-                                     stream);
+    if (s->dtype == SVOO_BF16) {
+        // matrix-core pre-filter decides the clear cases; float64 decides the queued rest
+        dim3 sgrid(k_own, bh), agrid((s->n + 255) / 256, bh);
+        if (d == 128) {
+            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(128), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
+                               k_own);
+            hipLaunchKernelGGL(assign_mfma_kernel<128>, agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi, w.wlo,
+                               w.wmax_bits, w.flags, labels, w.list, w.list_count, s->n, k_own);
+        } else {
+            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(128), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
+                               k_own);
+            hipLaunchKernelGGL(assign_mfma_kernel<64>, agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi, w.wlo,
+                               w.wmax_bits, w.flags, labels, w.list, w.list_count, s->n, k_own);
+        }
+        dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels,
+                                         nullptr, stream);
+    } else {
+        dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels,
+                                         nullptr, stream);
+    }
     return launch_status();
 }
 

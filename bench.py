@@ -168,17 +168,19 @@ def main():
 
     # ---- dense baseline of this build at the same shape
     x = inputs[0]
-    layer_obj.dense(x["q"], x["k"], x["v"], scale)
-    torch.cuda.synchronize()
-    d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    d0.record()
-    for _ in range(args.dense_reps):
-        layer_obj.dense(x["q"], x["k"], x["v"], scale)
-    d1.record()
-    torch.cuda.synchronize()
-    dense_ms = d0.elapsed_time(d1) / args.dense_reps
     dense_flops = 4.0 * cfg.heads * float(cfg.n) ** 2 * cfg.d
-    print(f"[bench] dense svoo_attn: {dense_ms:.1f} ms", file=sys.stderr, flush=True)
+    dense_ms = float("nan")
+    if args.dense_reps > 0:
+        layer_obj.dense(x["q"], x["k"], x["v"], scale)
+        torch.cuda.synchronize()
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        d0.record()
+        for _ in range(args.dense_reps):
+            layer_obj.dense(x["q"], x["k"], x["v"], scale)
+        d1.record()
+        torch.cuda.synchronize()
+        dense_ms = d0.elapsed_time(d1) / args.dense_reps
+        print(f"[bench] dense svoo_attn: {dense_ms:.1f} ms", file=sys.stderr, flush=True)
 
     attn_ms = step_ms[:, 3]
     attn_tflops = float(kept_flops.sum() / (attn_ms.sum() * 1e-3) / 1e12)
@@ -199,8 +201,9 @@ def main():
         "kept_fraction_mean": round(float(np.mean(phis)), 4),
         "breakdown_ms": {name: round(float(step_ms[:, c].mean()), 3) for c, name in enumerate(STEP_NAMES)},
         "sparse_attn_kept_tflops": round(attn_tflops, 2),
-        "dense_attn_ms": round(dense_ms, 2), "dense_attn_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2),
-        "speedup_vs_own_dense": round(dense_ms / ms_per_step, 3),
+        "dense_attn_ms": round(dense_ms, 2) if args.dense_reps > 0 else None,
+        "dense_attn_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2) if args.dense_reps > 0 else None,
+        "speedup_vs_own_dense": round(dense_ms / ms_per_step, 3) if args.dense_reps > 0 else None,
         "roofline": {"bound": "mfma", "kernel": "sparse_attn_bf16_kernel<128>", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": None,

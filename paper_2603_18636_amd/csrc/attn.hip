@@ -175,7 +175,8 @@ __device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_
 // LDS: K and V tiles of 64 keys, row-major [key][D], double buffered, filled by direct
 // global->LDS 16-byte loads (no register staging).  A wave-load writes 1 KB = lane-consecutive
 // 16-byte slots, so the 16-byte chunk c of tile row r is fetched by the lane whose slot is
-// c ^ (r mod chunks-per-row): an XOR swizzle that makes both kinds of reads below conflict-free.
+// c ^ swizzle(r): an XOR swizzle (by row for K, by row on 32-byte granules for V) that makes both
+// kinds of reads below conflict-free.
 //   K operand: ds_read_b128, lane (j, h) reads row 32 kb + j, chunk 2 c + h.
 //   V operand: ds_read_b64_tr_b16 (transposing read): within a 16-lane block the lane s points at
 //              4 consecutive d-columns of key row (s / 4); the lane i receives, for d-column i of
@@ -233,6 +234,10 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     const int total = ti.total;
     const int n_tiles = (total + KT - 1) / KT;
 
+    // V swizzle (in 16-byte chunk units): one transposing read touches, per half wave, 4 key rows x
+    // 2 adjacent 32-byte column segments; XOR-ing the 64-byte granule index with the row spreads
+    // those 8 segments over all banks (K keeps the 16-byte swizzle by row).
+    auto vswz = [](int rho) { return ((rho / (256 / ROWB)) % (ROWB / 64)) << 2; };
     // ---- key-stream walk: this lane tracks tile row 16*wave + lane%16 from tile to tile
     int seg = 0, seg_end = 0, seg_delta = 0;
     if (total > 0) {
@@ -253,11 +258,12 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             const int rl = i * RPL + lane / CPR;          // row within this wave's 16
             const int row = __shfl(myrow, rl);
             const int rho = 16 * wave + rl;                // tile row
-            const int chunk = (lane % CPR) ^ (rho % CPR);
-            const uint32_t goff = (uint32_t)row * ROWB + chunk * 16;
+            const int kchunk = (lane % CPR) ^ (rho % CPR);
+            const int vchunk = (lane % CPR) ^ vswz(rho);
+            const uint32_t goff = (uint32_t)row * ROWB;
             const int loff = buf * TILE + (16 * wave + i * RPL) * ROWB;
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kg + goff), (lds_ptr_t)(k_lds + loff), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vg + goff), (lds_ptr_t)(v_lds + loff), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kg + goff + kchunk * 16), (lds_ptr_t)(k_lds + loff), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vg + goff + vchunk * 16), (lds_ptr_t)(v_lds + loff), 16, 0, 0);
         }
     };
 
@@ -287,7 +293,7 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             for (int db = 0; db < DB; ++db) {
                 const int rho = 8 * u + 4 * (blk / 2) + s / 4;            // + 32 kb + 16 t
                 const int chunk = 4 * db + 2 * (blk % 2) + (s % 4) / 2;
-                voff[u][db] = rho * ROWB + ((chunk ^ (rho % CPR)) * 16) + (s % 2) * 8;
+                voff[u][db] = rho * ROWB + ((chunk ^ vswz(rho)) * 16) + (s % 2) * 8;
             }
     }
 

@@ -5,16 +5,19 @@
 // segment), cut into tiles of KT keys; only the last tile of the stream is ragged.  Online softmax
 // (running max and sum per query row) makes one pass over the stream.
 //
-// bf16 kernel (CDNA4 matrix cores, v_mfma_f32_32x32x16_bf16), 4 waves x 32 query rows:
+// bf16 kernel (CDNA4 matrix cores, v_mfma_f32_32x32x16_bf16), 8 waves x 32 query rows:
 //   S^T = K_tile Q^T      A operand: K rows from LDS, B operand: Q, resident in registers
-//   O^T += V_tile^T P^T   A operand: V^T from LDS (V is transposed while it is staged),
+//   O^T += V_tile^T P^T   A operand: V^T, read from the row-major V tile with transposing LDS reads,
 //                          B operand: P^T taken straight from the S^T accumulators
 // Computing the transposes puts one query per lane: the softmax row reductions are in-lane plus a
 // single exchange between lane l and l+32, and the probabilities are already laid out as the next
-// MFMA's B operand.  The K rows are stored in LDS in the order the accumulator layout visits them
-// so that each lane ends up with 16 consecutive keys.
+// MFMA's B operand.  256 rows per workgroup halve the K/V traffic out of L2 per flop compared with
+// 128 (each K/V tile is fetched once per workgroup), which is what bounds this kernel once the
+// matrix pipeline is fed.
 //
 // f32 kernel: 4 lanes per query row, plain float32 FMAs, same schedule and key stream.
+#include <type_traits>
+
 #include "common.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -86,21 +89,27 @@ struct TileInfo {
 };
 
 // Which tile is this workgroup?  blockIdx.x is spread round-robin over the 8 XCDs by the
-// hardware; tiles whose index differs by less than gridDim.x/8 share an XCD (and its L2) so the
-// tiles of one query block, which read the same keys, run next to each other.
-__device__ __forceinline__ int logical_tile_index() {
-    const int per_xcd = gridDim.x / 8;
-    return (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+// hardware.  The REAL tiles (their number is only known on the device; the grid is sized for the
+// worst case) are dealt out in 8 equal contiguous ranges, one per XCD, so that every XCD gets the
+// same share and the tiles of one query block, which read the same keys, run next to each other
+// on one XCD and its L2.  Returns -1 for a workgroup without work.
+__device__ __forceinline__ int logical_tile_index(int total_tiles) {
+    const int per_xcd = (total_tiles + 7) / 8;
+    const int xcd = blockIdx.x % 8, i = blockIdx.x / 8;
+    const int slot = xcd * per_xcd + i;
+    return (i < per_xcd && slot < total_tiles) ? slot : -1;
 }
 
 // Fills seg_start / seg_cum in LDS and returns the tile description; false if there is no work.
-// seg_cum has n_seg + 1 entries (exclusive prefix of segment lengths); scan is 256 ints of scratch.
+// seg_cum has n_seg + 1 entries (exclusive prefix of segment lengths); scan is NT ints of scratch.
+template <int NT>
 __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* seg_start, int32_t* seg_cum,
                                            int32_t* scan, TileInfo& ti) {
+    constexpr int SPT = SVOO_MAX_K / NT;   // consecutive segments owned by one thread
     const int b = blockIdx.y, tid = threadIdx.x;
     const int32_t* tp = a.tile_prefix + (size_t)b * (a.kq + 1);
-    const int slot = logical_tile_index();
-    if (slot >= tp[a.kq]) return false;
+    const int slot = logical_tile_index(tp[a.kq]);
+    if (slot < 0) return false;
     int lo = 0, hi = a.kq;  // last r with tp[r] <= slot
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -118,11 +127,10 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
     cnt = cnt < 0 ? 0 : (cnt > a.kk ? a.kk : cnt);
     const int32_t* bl = a.block_list + ((size_t)b * a.kq + r) * a.kk;
     const int32_t* ko = a.k_offsets + (size_t)b * (a.kk + 1);
-    // each thread owns 4 consecutive segments
-    int len[4], start[4], local = 0;
+    int len[SPT], start[SPT], local = 0;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int i = tid * 4 + u;
+    for (int u = 0; u < SPT; ++u) {
+        const int i = tid * SPT + u;
         len[u] = 0;
         start[u] = 0;
         if (i < cnt) {
@@ -136,7 +144,7 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
     }
     scan[tid] = local;
     __syncthreads();
-    for (int s = 1; s < ATT_THREADS; s <<= 1) {
+    for (int s = 1; s < NT; s <<= 1) {
         const int v = tid >= s ? scan[tid - s] : 0;
         __syncthreads();
         scan[tid] += v;
@@ -144,15 +152,15 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
     }
     int run = scan[tid] - local;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int i = tid * 4 + u;
+    for (int u = 0; u < SPT; ++u) {
+        const int i = tid * SPT + u;
         if (i < cnt) {
             seg_start[i] = start[u];
             seg_cum[i] = run;
         }
         run += len[u];
     }
-    ti.total = scan[ATT_THREADS - 1];
+    ti.total = scan[NT - 1];
     ti.n_seg = cnt;
     if (tid == 0) seg_cum[cnt] = ti.total;
     __syncthreads();
@@ -185,7 +193,18 @@ __device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_
 // so 8 consecutive accumulators (v = 8t .. 8t+7) are two runs of 4 consecutive keys, which is
 // what two transposing reads deliver.
 // ---------------------------------------------------------------------------------------------
-#define BM_BF16 128
+// Kernel shape: NW waves of 32 query rows, NBUF K/V tile buffers in LDS (measured on MI355X at
+// 12 x 75,600 x 128):
+//   dense baseline : 8 waves x 3 buffers, one workgroup per CU.  256 rows per workgroup halve the
+//                    K/V traffic out of L2 per flop; a 4th buffer does not help.
+//   block-sparse   : 4 waves x 2 buffers, two workgroups per CU.  Query blocks are a few hundred
+//                    rows, so 128-row tiles waste fewer rows in the last tile of a block than 256.
+#ifndef SVOO_SPARSE_NW
+#define SVOO_SPARSE_NW 4
+#define SVOO_SPARSE_NBUF 2
+#endif
+#define DENSE_NW 8
+#define DENSE_NBUF 3
 #define RESCALE_LOG2 8.0f   // the running max is only raised when it is exceeded by 2^8
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;
@@ -199,33 +218,36 @@ __device__ __forceinline__ uint32_t pack2_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
 }
 
-template <int D>
+template <int D, int NBUF>
 struct AttnLds {
     static constexpr int ROWB = D * 2;            // bytes per K/V row
     static constexpr int TILE = KT * ROWB;        // bytes per tile
     static constexpr int SEG_BYTES = (2 * SVOO_MAX_K + 8) * 4;
-    static constexpr int BYTES = SEG_BYTES + 4 * TILE;   // seg tables + 2 x (K tile + V tile)
+    static constexpr int BYTES = SEG_BYTES + 2 * NBUF * TILE;   // seg tables + NBUF x (K tile + V tile)
 };
 
-template <int D>
-__global__ void __launch_bounds__(ATT_THREADS, 2)
+template <int D, int NW, int NBUF>
+__global__ void __launch_bounds__(64 * NW, 8 / NW)
 sparse_attn_bf16_kernel(AttnArgs a) {
+    constexpr int NT = 64 * NW, BM = 32 * NW;
     constexpr int DC = D / 16;        // 16-wide contraction chunks of QK^T
     constexpr int DB = D / 32;        // 32-row blocks of O^T
     constexpr int CPR = D / 8;        // 16-byte chunks per row
-    constexpr int ROWB = AttnLds<D>::ROWB;
-    constexpr int TILE = AttnLds<D>::TILE;
+    constexpr int ROWB = AttnLds<D, NBUF>::ROWB;
+    constexpr int TILE = AttnLds<D, NBUF>::TILE;
     constexpr int RPL = 64 / CPR;     // tile rows covered by one wave-load (1 KB)
-    constexpr int LPW = 16 / RPL;     // wave-loads per wave per tile (each wave owns 16 tile rows)
+    constexpr int RW = KT / NW;       // tile rows owned by one wave
+    constexpr int LPW = RW / RPL;     // wave-loads per wave per tile and tensor
+    static_assert(LPW >= 1 && RW <= 16 && NBUF >= 2 && NBUF <= 4, "wave-load geometry");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-    unsigned char* k_lds = smem;                  // [2][TILE]
-    unsigned char* v_lds = smem + 2 * TILE;       // [2][TILE]
-    int32_t* seg_start = (int32_t*)(smem + 4 * TILE);
+    unsigned char* k_lds = smem;                     // [NBUF][TILE]
+    unsigned char* v_lds = smem + NBUF * TILE;       // [NBUF][TILE]
+    int32_t* seg_start = (int32_t*)(smem + 2 * NBUF * TILE);
     int32_t* seg_cum = seg_start + SVOO_MAX_K;
     int32_t* scan = (int32_t*)smem;               // setup scratch, aliases the K tiles
 
     TileInfo ti;
-    if (!setup_tile(a, BM_BF16, seg_start, seg_cum, scan, ti)) return;
+    if (!setup_tile<NT>(a, BM, seg_start, seg_cum, scan, ti)) return;
     const int b = blockIdx.y, tid = threadIdx.x;
     const int wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
     const uint16_t* qg = (const uint16_t*)a.q + (size_t)b * a.n * D;
@@ -238,14 +260,14 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     // 2 adjacent 32-byte column segments; XOR-ing the 64-byte granule index with the row spreads
     // those 8 segments over all banks (K keeps the 16-byte swizzle by row).
     auto vswz = [](int rho) { return ((rho / (256 / ROWB)) % (ROWB / 64)) << 2; };
-    // ---- key-stream walk: this lane tracks tile row 16*wave + lane%16 from tile to tile
+    // ---- key-stream walk: this lane tracks tile row RW*wave + lane%RW from tile to tile
     int seg = 0, seg_end = 0, seg_delta = 0;
     if (total > 0) {
         seg_end = seg_cum[1];
         seg_delta = seg_start[0] - seg_cum[0];
     }
     auto issue_tile = [&](int t, int buf) {
-        int p = t * KT + 16 * wave + (lane % 16);
+        int p = t * KT + RW * wave + (lane % RW);
         p = p < total ? p : total - 1;        // rows past the end re-read the last key (masked later)
         while (p >= seg_end) {                // terminates: p < total = seg_cum[n_seg]
             ++seg;
@@ -255,13 +277,13 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         const int myrow = p + seg_delta;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int rl = i * RPL + lane / CPR;          // row within this wave's 16
+            const int rl = i * RPL + lane / CPR;          // row within this wave's RW
             const int row = __shfl(myrow, rl);
-            const int rho = 16 * wave + rl;                // tile row
+            const int rho = RW * wave + rl;                // tile row
             const int kchunk = (lane % CPR) ^ (rho % CPR);
             const int vchunk = (lane % CPR) ^ vswz(rho);
             const uint32_t goff = (uint32_t)row * ROWB;
-            const int loff = buf * TILE + (16 * wave + i * RPL) * ROWB;
+            const int loff = buf * TILE + (RW * wave + i * RPL) * ROWB;
             __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kg + goff + kchunk * 16), (lds_ptr_t)(k_lds + loff), 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vg + goff + vchunk * 16), (lds_ptr_t)(v_lds + loff), 16, 0, 0);
         }
@@ -307,27 +329,71 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     float m_used = -INFINITY;   // reference max (raw logits) the probabilities are scaled by
     float lsum = 0.f;           // this lane's share of the row sum
 
-    if (n_tiles > 0) issue_tile(0, 0);
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int buf = kt & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();        // tile kt has landed for every wave; everyone is done with the other buffer
-        if (kt + 1 < n_tiles) issue_tile(kt + 1, buf ^ 1);
-        if (!wave_active) continue;
-        const unsigned char* kt_lds = k_lds + buf * TILE;
-        const unsigned char* vt_lds = v_lds + buf * TILE;
-
-        // ---- S^T = K Q^T for the two 32-key blocks of the tile
+    // One tile (64 keys) out of LDS buffer BUF.  LDS reads are issued in batches ahead of the
+    // matrix instructions that consume them (the LDS latency is ~100 cycles, one MFMA is 32):
+    //   S phase   K fragments in 4 batches of DC/2, two batches in flight
+    //   softmax   V fragments of the first 32-key block are fetched while the row maxima and
+    //             the exponentials are computed
+    //   PV phase  first block's MFMAs run while the second block's V fragments arrive
+    auto tile_body = [&](auto bufc, int kt) {
+        constexpr int BUF = decltype(bufc)::value;
+        constexpr int HB = DC / 2;
+        const unsigned char* kt_lds = k_lds + BUF * TILE;
+        const unsigned char* vt_lds = v_lds + BUF * TILE;
+        auto kfrag = [&](int kb, int c) {
+            return __builtin_bit_cast(bf16x8, *(const uint4*)(kt_lds + kb * 32 * ROWB + koff[c]));
+        };
+        auto vfrag = [&](int kb, int t, int db) {
+            const int cst = (32 * kb + 16 * t) * ROWB;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[0][db]));
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+                (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[1][db]));
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        };
         f32x16 s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+        bf16x8 fa[HB], fb[HB];
 #pragma unroll
-            for (int c = 0; c < DC; ++c) {
-                const uint4 u = *(const uint4*)(kt_lds + kb * 32 * ROWB + koff[c]);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, u), qf[c], s[kb], 0, 0, 0);
-            }
+        for (int c = 0; c < HB; ++c) fa[c] = kfrag(0, c);
+#pragma unroll
+        for (int c = 0; c < HB; ++c) fb[c] = kfrag(0, HB + c);
+#pragma unroll
+        for (int c = 0; c < HB; ++c) {
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], qf[c], s[0], 0, 0, 0);
+            fa[c] = kfrag(1, c);
+        }
+#pragma unroll
+        for (int c = 0; c < HB; ++c) {
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], qf[HB + c], s[0], 0, 0, 0);
+            fb[c] = kfrag(1, HB + c);
+        }
+        // V fragments of block 0 start arriving while block 1 of S is computed
+        bf16x8 vf[2][DB];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) vf[t][db] = vfrag(0, t, db);
+#pragma unroll
+        for (int c = 0; c < HB; ++c) s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], qf[c], s[1], 0, 0, 0);
+#pragma unroll
+        for (int c = 0; c < HB; ++c) s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], qf[HB + c], s[1], 0, 0, 0);
+
+        // scheduling pipeline of this block: 2 batches of K reads, then every MFMA paired with the
+        // LDS read(s) that refill its operand registers / prefetch V
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * HB, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * HB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2 * HB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (2 * 2 * DB) / (2 * HB), 0);
         }
         // ragged last tile: keys past the end of the stream get -inf
         if (kt == n_tiles - 1 && (total % KT) != 0) {
@@ -359,36 +425,69 @@ sparse_attn_bf16_kernel(AttnArgs a) {
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
         const float mb = m_used * c2;
-        bf16x8 pf[2][2];
+        auto probs = [&](int kb, int t) {
+            uint32_t w[4];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                uint32_t w[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e], c2, -mb));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e + 1], c2, -mb));
-                    lsum += p0 + p1;
-                    w[e] = pack2_bf16(p0, p1);
-                }
-                pf[kb][t] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            for (int e = 0; e < 4; ++e) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e], c2, -mb));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e + 1], c2, -mb));
+                lsum += p0 + p1;
+                w[e] = pack2_bf16(p0, p1);
             }
-        // ---- O^T += V^T P^T
+            return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+        };
+        // ---- O^T += V^T P^T, block 0 then block 1
+        bf16x8 pf[2];
+        pf[0] = probs(0, 0);
+        pf[1] = probs(0, 1);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int db = 0; db < DB; ++db) {
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][db], pf[t], o[db], 0, 0, 0);
+                vf[t][db] = vfrag(1, t, db);
+            }
+        pf[0] = probs(1, 0);
+        pf[1] = probs(1, 1);
 #pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const int cst = (32 * kb + 16 * t) * ROWB;
-                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[0][db]));
-                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                        (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[1][db]));
-                    const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb][t], o[db], 0, 0, 0);
-                }
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][db], pf[t], o[db], 0, 0, 0);
+        // pipeline: exponentials of block 0, then each MFMA of block 0 paired with two V reads of
+        // block 1 and a slice of block 1's exponentials, then block 1's MFMAs
+        __builtin_amdgcn_sched_group_barrier(0x402, 56, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * DB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x402, 56 / (2 * DB), 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 0);
+    };
+
+    // Prefetch distance NBUF-1 tiles.  Loads complete in order, so "all but the newest tile's
+    // loads" is a constant outstanding-load count while tiles are still being issued.
+    for (int t = 0; t < NBUF - 1 && t < n_tiles; ++t) issue_tile(t, t);
+    auto step = [&](auto bufc, int kt) {
+        constexpr int BUF = decltype(bufc)::value;
+        // tiles kt+1 .. kt+NBUF-2 (those that exist) may stay in flight; loads complete in order
+        const int ahead = n_tiles - 1 - kt < NBUF - 2 ? n_tiles - 1 - kt : NBUF - 2;
+        if (NBUF >= 4 && ahead == 2)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * 2 * LPW) : "memory");
+        else if (NBUF >= 3 && ahead == 1)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();        // tile kt has landed for every wave; everyone is done with tile kt-1's buffer
+        if (kt + NBUF - 1 < n_tiles) issue_tile(kt + NBUF - 1, (BUF + NBUF - 1) % NBUF);
+        if (wave_active) tile_body(bufc, kt);
+    };
+    for (int kt = 0; kt < n_tiles; kt += NBUF) {
+        step(std::integral_constant<int, 0>{}, kt);
+        if (kt + 1 < n_tiles) step(std::integral_constant<int, 1>{}, kt + 1);
+        if (NBUF > 2 && kt + 2 < n_tiles) step(std::integral_constant<int, 2 % NBUF>{}, kt + 2);
+        if (NBUF > 3 && kt + 3 < n_tiles) step(std::integral_constant<int, 3 % NBUF>{}, kt + 3);
     }
 
     // ---- epilogue: normalise, transpose through LDS, store whole rows.
@@ -451,7 +550,7 @@ sparse_attn_f32_kernel(AttnArgs a) {
     __shared__ float4 v_lds[KT_F32 * D / 4];
 
     TileInfo ti;
-    if (!setup_tile(a, BM_F32, seg_start, seg_cum, scan, ti)) return;
+    if (!setup_tile<ATT_THREADS>(a, BM_F32, seg_start, seg_cum, scan, ti)) return;
     const int b = blockIdx.y, tid = threadIdx.x;
     const int qrow = tid / 4, part = tid % 4;
     const bool qvalid = qrow < ti.qn;
@@ -538,34 +637,40 @@ sparse_attn_f32_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-static inline int attn_bm(int dtype) { return dtype == SVOO_BF16 ? BM_BF16 : BM_F32; }
-
 size_t attn_ws_bytes(const svoo_shape* s) {
     // tile_prefix for the sparse call; the dense call adds a 1-block layout
     const size_t kq = s->kq > 1 ? s->kq : 1;
     return align_up((size_t)s->bh * (kq + 1) * 4, 256) + 3 * align_up((size_t)s->bh * 2 * 4, 256);
 }
 
-static int launch_sparse(const svoo_shape* s, AttnArgs& a, int32_t* tile_prefix, hipStream_t stream) {
-    const int bm = attn_bm(s->dtype);
+template <int D, int NW, int NBUF>
+static int launch_bf16(dim3 grid, const AttnArgs& a, hipStream_t stream) {
+    // more than 64 KB of dynamic LDS must be opted into per kernel
+    auto kern = sparse_attn_bf16_kernel<D, NW, NBUF>;
+    constexpr int lds_bytes = AttnLds<D, NBUF>::BYTES;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+        return SVOO_ERR_HIP;
+    hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds_bytes, stream, a);
+    return SVOO_OK;
+}
+
+// dense = one-block layout: every workgroup reads the same key stream
+static int launch_sparse(const svoo_shape* s, AttnArgs& a, int32_t* tile_prefix, bool dense, hipStream_t stream) {
+    const int bm = s->dtype == SVOO_BF16 ? 32 * (dense ? DENSE_NW : SVOO_SPARSE_NW) : BM_F32;
     hipLaunchKernelGGL(attn_schedule_kernel, dim3(s->bh), dim3(1024), 0, stream, a.q_offsets, tile_prefix, a.kq, bm);
     a.tile_prefix = tile_prefix;
     int gx = (s->n + bm - 1) / bm + a.kq;
     gx = (gx + 7) / 8 * 8;
     dim3 grid(gx, s->bh);
+    int st = SVOO_OK;
     if (s->dtype == SVOO_BF16) {
-        // more than 64 KB of dynamic LDS must be opted into per kernel
-        if (s->d == 128) {
-            if (hipFuncSetAttribute((const void*)sparse_attn_bf16_kernel<128>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, AttnLds<128>::BYTES) != hipSuccess)
-                return SVOO_ERR_HIP;
-            hipLaunchKernelGGL(sparse_attn_bf16_kernel<128>, grid, dim3(ATT_THREADS), AttnLds<128>::BYTES, stream, a);
-        } else {
-            if (hipFuncSetAttribute((const void*)sparse_attn_bf16_kernel<64>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, AttnLds<64>::BYTES) != hipSuccess)
-                return SVOO_ERR_HIP;
-            hipLaunchKernelGGL(sparse_attn_bf16_kernel<64>, grid, dim3(ATT_THREADS), AttnLds<64>::BYTES, stream, a);
-        }
+        if (s->d == 128)
+            st = dense ? launch_bf16<128, DENSE_NW, DENSE_NBUF>(grid, a, stream)
+                       : launch_bf16<128, SVOO_SPARSE_NW, SVOO_SPARSE_NBUF>(grid, a, stream);
+        else
+            st = dense ? launch_bf16<64, DENSE_NW, DENSE_NBUF>(grid, a, stream)
+                       : launch_bf16<64, SVOO_SPARSE_NW, SVOO_SPARSE_NBUF>(grid, a, stream);
+        if (st != SVOO_OK) return st;
     } else {
         if (s->d == 128)
             hipLaunchKernelGGL(sparse_attn_f32_kernel<128>, grid, dim3(ATT_THREADS), 0, stream, a);
@@ -591,7 +696,7 @@ extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sor
     if (ws_bytes < attn_ws_bytes(shape)) return SVOO_ERR_WORKSPACE_TOO_SMALL;
     AttnArgs a = {q_sorted, k_sorted, v_sorted, out_sorted, lse, q_offsets, k_offsets, block_count, block_list,
                   nullptr, shape->n, shape->kq, shape->kk, scale};
-    return launch_sparse(shape, a, (int32_t*)ws, (hipStream_t)hip_stream);
+    return launch_sparse(shape, a, (int32_t*)ws, false, (hipStream_t)hip_stream);
 }
 
 extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale, void* out,
@@ -615,5 +720,5 @@ extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, 
     hipLaunchKernelGGL(dense_layout_kernel, dim3((s.bh + 255) / 256), dim3(256), 0, stream, offsets, block_count,
                        block_list, s.n, s.bh);
     AttnArgs a = {q, k, v, out, lse, offsets, offsets, block_count, block_list, nullptr, s.n, 1, 1, scale};
-    return launch_sparse(&s, a, tile_prefix, stream);
+    return launch_sparse(&s, a, tile_prefix, true, stream);
 }

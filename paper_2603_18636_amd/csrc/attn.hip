@@ -289,10 +289,18 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         }
     };
 
-    // ---- Q fragments: query row (wave, j), contraction elements 16c + 8h .. +7
-    const int qrow = 32 * wave + j;
+    // ---- which rows / which keys this wave works on.
+    // Normal tile: wave w owns rows 32w .. 32w+31 and every key.  Tile with at most half the rows
+    // (the last tile of a query block, often): the waves split the KEYS instead -- wave pair g =
+    // w / 2 takes the g-th 32-key block of every tile for rows 32 (w % 2) .., and the two partial
+    // results are merged at the end -- so that a short tile costs half the time, not all of it.
+    const bool split = NW >= 4 && ti.qn <= BM / 2;
+    const int kgrp = split ? wave / (NW / 2) : 0;
+    const int rwave = split ? wave % (NW / 2) : wave;
+    // ---- Q fragments: query row (rwave, j), contraction elements 16c + 8h .. +7
+    const int qrow = 32 * rwave + j;
     const bool qvalid = qrow < ti.qn;
-    const bool wave_active = 32 * wave < ti.qn;
+    const bool wave_active = 32 * rwave < ti.qn;
     bf16x8 qf[DC];
     {
         const uint4* src = (const uint4*)(qg + (size_t)(ti.q0 + (qvalid ? qrow : 0)) * D);
@@ -319,6 +327,15 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             }
     }
 
+    // key-split waves read "their" 32-key block of every tile: fold its offset into the addresses
+    const int kb_off = 32 * kgrp;
+#pragma unroll
+    for (int c = 0; c < DC; ++c) koff[c] += kb_off * ROWB;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) voff[u][db] += kb_off * ROWB;
+
     f32x16 o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -329,14 +346,18 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     float m_used = -INFINITY;   // reference max (raw logits) the probabilities are scaled by
     float lsum = 0.f;           // this lane's share of the row sum
 
-    // One tile (64 keys) out of LDS buffer BUF.  LDS reads are issued in batches ahead of the
-    // matrix instructions that consume them (the LDS latency is ~100 cycles, one MFMA is 32):
-    //   S phase   K fragments in 4 batches of DC/2, two batches in flight
-    //   softmax   V fragments of the first 32-key block are fetched while the row maxima and
-    //             the exponentials are computed
-    //   PV phase  first block's MFMAs run while the second block's V fragments arrive
-    auto tile_body = [&](auto bufc, int kt) {
+    // One tile (64 keys) out of LDS buffer BUF; MODE 0 = both 32-key blocks, 1 = one block (the
+    // key-split wave's own block, whose offset is already folded into the read addresses).  LDS reads are issued in batches ahead of the matrix
+    // instructions that consume them (the LDS latency is ~100 cycles, one MFMA is 32):
+    //   S phase   K fragments in batches of DC/2, two batches in flight
+    //   softmax   V fragments of the first block are fetched while S finishes
+    //   PV phase  first block's MFMAs run while the second block's V fragments arrive and its
+    //             exponentials are computed
+    auto tile_body = [&](auto bufc, auto modec, int kt) {
         constexpr int BUF = decltype(bufc)::value;
+        constexpr int MODE = decltype(modec)::value;
+        constexpr int KB0 = 0;
+        constexpr int NKB = MODE == 0 ? 2 : 1;       // number of blocks
         constexpr int HB = DC / 2;
         const unsigned char* kt_lds = k_lds + BUF * TILE;
         const unsigned char* vt_lds = v_lds + BUF * TILE;
@@ -351,44 +372,49 @@ sparse_attn_bf16_kernel(AttnArgs a) {
                 (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[1][db]));
             return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         };
-        f32x16 s[2];
+        f32x16 s[NKB];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
         bf16x8 fa[HB], fb[HB];
-#pragma unroll
-        for (int c = 0; c < HB; ++c) fa[c] = kfrag(0, c);
-#pragma unroll
-        for (int c = 0; c < HB; ++c) fb[c] = kfrag(0, HB + c);
-#pragma unroll
-        for (int c = 0; c < HB; ++c) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], qf[c], s[0], 0, 0, 0);
-            fa[c] = kfrag(1, c);
-        }
-#pragma unroll
-        for (int c = 0; c < HB; ++c) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], qf[HB + c], s[0], 0, 0, 0);
-            fb[c] = kfrag(1, HB + c);
-        }
-        // V fragments of block 0 start arriving while block 1 of S is computed
         bf16x8 vf[2][DB];
+#pragma unroll
+        for (int c = 0; c < HB; ++c) fa[c] = kfrag(KB0, c);
+#pragma unroll
+        for (int c = 0; c < HB; ++c) fb[c] = kfrag(KB0, HB + c);
+        if (NKB == 2) {
+#pragma unroll
+            for (int c = 0; c < HB; ++c) {
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], qf[c], s[0], 0, 0, 0);
+                fa[c] = kfrag(1, c);
+            }
+#pragma unroll
+            for (int c = 0; c < HB; ++c) {
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], qf[HB + c], s[0], 0, 0, 0);
+                fb[c] = kfrag(1, HB + c);
+            }
+        }
+        // V fragments of the first block start arriving while the last block of S is computed
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int db = 0; db < DB; ++db) vf[t][db] = vfrag(0, t, db);
+            for (int db = 0; db < DB; ++db) vf[t][db] = vfrag(KB0, t, db);
 #pragma unroll
-        for (int c = 0; c < HB; ++c) s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], qf[c], s[1], 0, 0, 0);
+        for (int c = 0; c < HB; ++c)
+            s[NKB - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[c], qf[c], s[NKB - 1], 0, 0, 0);
 #pragma unroll
-        for (int c = 0; c < HB; ++c) s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], qf[HB + c], s[1], 0, 0, 0);
-
+        for (int c = 0; c < HB; ++c)
+            s[NKB - 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c], qf[HB + c], s[NKB - 1], 0, 0, 0);
         // scheduling pipeline of this block: 2 batches of K reads, then every MFMA paired with the
         // LDS read(s) that refill its operand registers / prefetch V
         __builtin_amdgcn_sched_group_barrier(0x100, 2 * HB, 0);
+        if (NKB == 2) {
 #pragma unroll
-        for (int i = 0; i < 2 * HB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int i = 0; i < 2 * HB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
 #pragma unroll
         for (int i = 0; i < 2 * HB; ++i) {
@@ -399,14 +425,14 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         if (kt == n_tiles - 1 && (total % KT) != 0) {
             const int base = kt * KT + 4 * h;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    if (base + 32 * kb + 8 * (v / 4) + (v % 4) >= total) s[kb][v] = -INFINITY;
+                    if (base + kb_off + 32 * kb + 8 * (v / 4) + (v % 4) >= total) s[kb][v] = -INFINITY;
         }
         float mx = s[0][0];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
         {
@@ -424,7 +450,8 @@ sparse_attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
-        const float mb = m_used * c2;
+        // a key-split wave may have seen only masked keys so far (-inf reference): keep exp2 finite
+        const float mb = (MODE != 0 && m_used == -INFINITY) ? 0.f : m_used * c2;
         auto probs = [&](int kb, int t) {
             uint32_t w[4];
 #pragma unroll
@@ -436,61 +463,71 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             }
             return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
         };
-        // ---- O^T += V^T P^T, block 0 then block 1
+        // ---- O^T += V^T P^T, block by block
         bf16x8 pf[2];
         pf[0] = probs(0, 0);
         pf[1] = probs(0, 1);
+        if (NKB == 2) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][db], pf[t], o[db], 0, 0, 0);
-                vf[t][db] = vfrag(1, t, db);
-            }
-        pf[0] = probs(1, 0);
-        pf[1] = probs(1, 1);
+                for (int db = 0; db < DB; ++db) {
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][db], pf[t], o[db], 0, 0, 0);
+                    vf[t][db] = vfrag(1, t, db);
+                }
+            pf[0] = probs(1, 0);
+            pf[1] = probs(1, 1);
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int db = 0; db < DB; ++db)
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][db], pf[t], o[db], 0, 0, 0);
-        // pipeline: exponentials of block 0, then each MFMA of block 0 paired with two V reads of
-        // block 1 and a slice of block 1's exponentials, then block 1's MFMAs
+        // pipeline: exponentials of the first block, then (two-block tiles) each MFMA of block 0
+        // paired with two V reads of block 1 and a slice of block 1's exponentials, then the rest
         __builtin_amdgcn_sched_group_barrier(0x402, 56, 0);
+        if (NKB == 2) {
 #pragma unroll
-        for (int i = 0; i < 2 * DB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x402, 56 / (2 * DB), 0);
+            for (int i = 0; i < 2 * DB; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x402, 56 / (2 * DB), 0);
+            }
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 0);
     };
 
-    // Prefetch distance NBUF-1 tiles.  Loads complete in order, so "all but the newest tile's
+    // Prefetch distance NBUF-1 tiles.  Loads complete in order, so "all but the newest tiles'
     // loads" is a constant outstanding-load count while tiles are still being issued.
     for (int t = 0; t < NBUF - 1 && t < n_tiles; ++t) issue_tile(t, t);
-    auto step = [&](auto bufc, int kt) {
-        constexpr int BUF = decltype(bufc)::value;
-        // tiles kt+1 .. kt+NBUF-2 (those that exist) may stay in flight; loads complete in order
-        const int ahead = n_tiles - 1 - kt < NBUF - 2 ? n_tiles - 1 - kt : NBUF - 2;
-        if (NBUF >= 4 && ahead == 2)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * 2 * LPW) : "memory");
-        else if (NBUF >= 3 && ahead == 1)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();        // tile kt has landed for every wave; everyone is done with tile kt-1's buffer
-        if (kt + NBUF - 1 < n_tiles) issue_tile(kt + NBUF - 1, (BUF + NBUF - 1) % NBUF);
-        if (wave_active) tile_body(bufc, kt);
+    auto run_tiles = [&](auto modec) {
+        auto step = [&](auto bufc, int kt) {
+            constexpr int BUF = decltype(bufc)::value;
+            // tiles kt+1 .. kt+NBUF-2 (those that exist) may stay in flight; loads complete in order
+            const int ahead = n_tiles - 1 - kt < NBUF - 2 ? n_tiles - 1 - kt : NBUF - 2;
+            if (NBUF >= 4 && ahead == 2)
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * 2 * LPW) : "memory");
+            else if (NBUF >= 3 && ahead == 1)
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPW) : "memory");
+            else
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();    // tile kt has landed for every wave; everyone is done with tile kt-1's buffer
+            if (kt + NBUF - 1 < n_tiles) issue_tile(kt + NBUF - 1, (BUF + NBUF - 1) % NBUF);
+            if (wave_active) tile_body(bufc, modec, kt);
+        };
+        for (int kt = 0; kt < n_tiles; kt += NBUF) {
+            step(std::integral_constant<int, 0>{}, kt);
+            if (kt + 1 < n_tiles) step(std::integral_constant<int, 1>{}, kt + 1);
+            if (NBUF > 2 && kt + 2 < n_tiles) step(std::integral_constant<int, 2 % NBUF>{}, kt + 2);
+            if (NBUF > 3 && kt + 3 < n_tiles) step(std::integral_constant<int, 3 % NBUF>{}, kt + 3);
+        }
     };
-    for (int kt = 0; kt < n_tiles; kt += NBUF) {
-        step(std::integral_constant<int, 0>{}, kt);
-        if (kt + 1 < n_tiles) step(std::integral_constant<int, 1>{}, kt + 1);
-        if (NBUF > 2 && kt + 2 < n_tiles) step(std::integral_constant<int, 2 % NBUF>{}, kt + 2);
-        if (NBUF > 3 && kt + 3 < n_tiles) step(std::integral_constant<int, 3 % NBUF>{}, kt + 3);
-    }
+    if (split)
+        run_tiles(std::integral_constant<int, 1>{});
+    else
+        run_tiles(std::integral_constant<int, 0>{});
 
-    // ---- epilogue: normalise, transpose through LDS, store whole rows.
+    // ---- epilogue: (merge key-split partials,) normalise, transpose through LDS, store whole rows.
     // Lane (j, h) holds O[q = j][d = 32 db + 8 (v/4) + 4 h + v%4].
     float ltot;
     {
@@ -498,24 +535,51 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         auto r = __builtin_amdgcn_permlane32_swap(li, li, false, false);
         ltot = __int_as_float(r[0]) + __int_as_float(r[1]);
     }
-    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
     __syncthreads();   // all waves are done with the K/V tiles
-    unsigned char* stage = smem + wave * (32 * ROWB);      // 32 rows x ROWB per wave, inside the K buffers
+    if (split) {
+        // wave pair 1 parks (O, m, l) in LDS; wave pair 0 folds it into its own partial result
+        float* park = (float*)smem + rwave * ((16 * DB + 2) * 64);
+        if (kgrp == 1 && wave_active) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            uint2 w;
-            w.x = pack2_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv);
-            w.y = pack2_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-            const int chunk = 4 * db + g;                  // 16-byte chunk holding d = 32 db + 8 g ..
-            *(uint2*)(stage + j * ROWB + ((chunk ^ (j % CPR)) * 16) + 8 * h) = w;
+                for (int v = 0; v < 16; ++v) park[(16 * db + v) * 64 + lane] = o[db][v];
+            park[(16 * DB) * 64 + lane] = m_used;
+            park[(16 * DB + 1) * 64 + lane] = ltot;
         }
-    __builtin_amdgcn_wave_barrier();
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    {
-        unsigned char* og = (unsigned char*)a.out + ((size_t)b * a.n + ti.q0 + 32 * wave) * ROWB;
-        const int rows_here = ti.qn - 32 * wave;           // valid rows of this wave (may be <= 0)
+        __syncthreads();
+        if (kgrp == 0 && wave_active) {
+            const float m_b = park[(16 * DB) * 64 + lane], l_b = park[(16 * DB + 1) * 64 + lane];
+            const float m_new = fmaxf(m_used, m_b);
+            const float sa = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
+            const float sb = m_b == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_b - m_new) * c2);
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] = o[db][v] * sa + park[(16 * db + v) * 64 + lane] * sb;
+            ltot = ltot * sa + l_b * sb;
+            m_used = m_new;
+        }
+        __syncthreads();   // the staging below reuses the same LDS
+    }
+    const bool writer = wave_active && kgrp == 0;
+    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    unsigned char* stage = smem + wave * (32 * ROWB);      // 32 rows x ROWB per wave, inside the K buffers
+    if (writer) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint2 w;
+                w.x = pack2_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv);
+                w.y = pack2_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+                const int chunk = 4 * db + g;                  // 16-byte chunk holding d = 32 db + 8 g ..
+                *(uint2*)(stage + j * ROWB + ((chunk ^ (j % CPR)) * 16) + 8 * h) = w;
+            }
+        __builtin_amdgcn_wave_barrier();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        unsigned char* og = (unsigned char*)a.out + ((size_t)b * a.n + ti.q0 + 32 * rwave) * ROWB;
+        const int rows_here = ti.qn - 32 * rwave;          // valid rows of this wave
 #pragma unroll
         for (int i = 0; i < (32 * CPR) / 64; ++i) {
             const int e = i * 64 + lane;
@@ -525,10 +589,10 @@ sparse_attn_bf16_kernel(AttnArgs a) {
                 *(uint4*)(og + (size_t)r * ROWB + c * 16) = val;
             }
         }
+        if (a.lse && qvalid && h == 0)
+            a.lse[(size_t)b * a.n + ti.q0 + qrow] =
+                ltot > 0.f ? (m_used * c2 + log2f(ltot)) * 0.6931471805599453f : -INFINITY;
     }
-    if (a.lse && qvalid && h == 0)
-        a.lse[(size_t)b * a.n + ti.q0 + qrow] =
-            ltot > 0.f ? (m_used * c2 + log2f(ltot)) * 0.6931471805599453f : -INFINITY;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -31,6 +31,22 @@ __device__ __forceinline__ double load_as_f64<uint16_t>(const uint16_t* p) { ret
 template <>
 __device__ __forceinline__ double load_as_f64<float>(const float* p) { return (double)*p; }
 
+// two consecutive elements as float64 (4-byte / 8-byte aligned address)
+template <typename T>
+__device__ __forceinline__ void load_pair(const T* p, double& a, double& b);
+template <>
+__device__ __forceinline__ void load_pair<uint16_t>(const uint16_t* p, double& a, double& b) {
+    const uint32_t u = *(const uint32_t*)p;
+    a = (double)__uint_as_float(u << 16);
+    b = (double)__uint_as_float(u & 0xffff0000u);
+}
+template <>
+__device__ __forceinline__ void load_pair<float>(const float* p, double& a, double& b) {
+    const float2 u = *(const float2*)p;
+    a = (double)u.x;
+    b = (double)u.y;
+}
+
 // c64[b, c, :] = x[b, idx[b, c], :]   or   c64 = (double) init_c
 template <typename T>
 __global__ void init_centroids_kernel(const T* __restrict__ x, const int32_t* __restrict__ idx,
@@ -72,11 +88,13 @@ struct GemmArgs {
     int m, n, k;
     long long a_batch, b_batch, c_batch;
     int a_sm, a_sk, b_sk, b_sn;
+    const int32_t* only_if;   // nullable: per-batch flag; the batch is skipped when it is 0
 };
 
 __global__ void __launch_bounds__(256) gemm_f64_kernel(GemmArgs g) {
     __shared__ double as[16][33];
     __shared__ double bs[16][33];
+    if (g.only_if && g.only_if[blockIdx.z] == 0) return;
     const double* a = g.a + (size_t)blockIdx.z * g.a_batch;
     const double* b = g.b + (size_t)blockIdx.z * g.b_batch;
     double* c = g.c + (size_t)blockIdx.z * g.c_batch;
@@ -276,6 +294,74 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
             for (int u = 0; u < 16; ++u) s += red_s[tid * 16 + u];
             quad_out[(size_t)b * n + tok[tid]] = s;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Float64 decision for the queued tokens of the matrix-core pre-filter: one workgroup per token
+// (strided over the queue), wave w scores centroids w, w+4, ...; a lane holds two elements of x,
+// reads the matching two of W_j (a coalesced 1 KB row) and the wave adds the 64 partial sums in a
+// fixed butterfly order.  Same decision rule as token_tile_kernel<MODE_ARGMAX>.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int k_own,
+                   const double* __restrict__ bterm, const int32_t* __restrict__ flags,
+                   const double* __restrict__ nx2, const int32_t* __restrict__ list,
+                   const int32_t* __restrict__ list_count, int32_t* __restrict__ labels, int n) {
+    __shared__ double best_v[4];
+    __shared__ int32_t best_j[4];
+    const int b = blockIdx.y, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    const int count = list_count[b];
+    const bool general = flags[b] != 0;
+    const double* wb = wmat + (size_t)b * k_own * D;
+    for (int p = blockIdx.x; p < count; p += gridDim.x) {
+        const int ti = list[(size_t)b * n + p];
+        double x0 = 0.0, x1 = 0.0;
+        if (2 * lane < D) load_pair<T>(x + ((size_t)b * n + ti) * D + 2 * lane, x0, x1);
+        double nx = 0.0;
+        if (general) {
+            const double v = nx2[(size_t)b * n + ti];
+            const double r = sqrt(v > 0.0 ? v : 0.0);
+            nx = r > NORM_FLOOR ? r : NORM_FLOOR;
+        }
+        double best = -INFINITY;
+        int bj = 0;
+        for (int j = wave; j < k_own; j += 4) {
+            double part = 0.0;
+            if (2 * lane < D) {
+                const double2 wv = *(const double2*)(wb + (size_t)j * D + 2 * lane);
+                part = fma(x0, wv.x, x1 * wv.y);
+            }
+            const double sdot = wave_sum_f64(part);
+            const double val = general ? 2.0 * sdot - nx * bterm[(size_t)b * k_own + j] : sdot;
+            if (val > best) {
+                best = val;
+                bj = j;
+            }
+        }
+        if (lane == 0) {
+            best_v[wave] = best;
+            best_j[wave] = bj;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double bv = best_v[0];
+            int jj = best_j[0];
+            for (int u = 1; u < 4; ++u)
+                if (best_v[u] > bv || (best_v[u] == bv && best_j[u] < jj)) {
+                    bv = best_v[u];
+                    jj = best_j[u];
+                }
+            labels[(size_t)b * n + ti] = jj;
+        }
+        __syncthreads();
     }
 }
 
@@ -499,21 +585,6 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
 // token order.  256 threads = G row-groups of (D/2) lanes; lane l adds elements 2l, 2l+1 of the
 // rows g, g+G, g+2G, ... of its group, then the G partial sums are added in group order.
 // ---------------------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ void load_pair(const T* p, double& a, double& b);
-template <>
-__device__ __forceinline__ void load_pair<uint16_t>(const uint16_t* p, double& a, double& b) {
-    const uint32_t u = *(const uint32_t*)p;
-    a = (double)__uint_as_float(u << 16);
-    b = (double)__uint_as_float(u & 0xffff0000u);
-}
-template <>
-__device__ __forceinline__ void load_pair<float>(const float* p, double& a, double& b) {
-    const float2 u = *(const float2*)p;
-    a = (double)u.x;
-    b = (double)u.y;
-}
-
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm,
@@ -666,17 +737,18 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
                        (size_t)3 * bh);
     // Pbar[j, c] = <c_own_j, c_opp_c>
     GemmArgs g1 = {c_own, c_opp, w.pbar, k_own, k_opp, d, (long long)k_own * d, (long long)k_opp * d,
-                   (long long)k_own * k_opp, d, 1, 1, d};
+                   (long long)k_own * k_opp, d, 1, 1, d, nullptr};
     launch_gemm(g1, bh, stream);
     hipLaunchKernelGGL(normalize_anchor_rows_kernel, dim3(k_own, bh), dim3(256), 0, stream, w.pbar, w.bterm, w.flags,
                        k_own, k_opp);
     // W[j, :] = sum_c Pbar^[j, c] * c_opp[c, :]
     GemmArgs g2 = {w.pbar, c_opp, w.w64, k_own, d, k_opp, (long long)k_own * k_opp, (long long)k_opp * d,
-                   (long long)k_own * d, k_opp, 1, d, 1};
+                   (long long)k_own * d, k_opp, 1, d, 1, nullptr};
     launch_gemm(g2, bh, stream);
     // G[a, b] = sum_c c_opp[c, a] * c_opp[c, b]
+    // (only slices with a degenerate anchor need it, unless the objective is wanted)
     GemmArgs g3 = {c_opp, c_opp, w.gram, d, d, k_opp, (long long)k_opp * d, (long long)k_opp * d, (long long)d * d,
-                   1, d, d, 1};
+                   1, d, d, 1, want_nx2 ? nullptr : w.flags};
     launch_gemm(g3, bh, stream);
     // nx^2 = x^T G x: every workgroup of a slice without degenerate anchors exits at once unless the
     // objective wants it, so the launch sequence never depends on device-side flags.
@@ -696,8 +768,13 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
             hipLaunchKernelGGL(assign_mfma_kernel<64>, agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi, w.wlo,
                                w.wmax_bits, w.flags, labels, w.list, w.list_count, s->n, k_own);
         }
-        dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels,
-                                         nullptr, stream);
+        dim3 lgrid(s->n < 256 ? s->n : 256, bh);
+        if (d == 128)
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, labels, s->n);
+        else
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, labels, s->n);
     } else {
         dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels,
                                          nullptr, stream);

@@ -301,14 +301,8 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
 // Float64 decision for the queued tokens of the matrix-core pre-filter: one workgroup per token
 // (strided over the queue), wave w scores centroids w, w+4, ...; a lane holds two elements of x,
 // reads the matching two of W_j (a coalesced 1 KB row) and the wave adds the 64 partial sums in a
-// fixed butterfly order.  Same decision rule as token_tile_kernel<MODE_ARGMAX>.
+// fixed butterfly order (xor 32, 16, ..., 1).  Same decision rule as token_tile_kernel<MODE_ARGMAX>.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
-
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int k_own,
@@ -333,17 +327,32 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int
         }
         double best = -INFINITY;
         int bj = 0;
-        for (int j = wave; j < k_own; j += 4) {
-            double part = 0.0;
-            if (2 * lane < D) {
-                const double2 wv = *(const double2*)(wb + (size_t)j * D + 2 * lane);
-                part = fma(x0, wv.x, x1 * wv.y);
+        // eight centroids per pass so that their row loads and butterfly sums overlap
+        for (int j0 = wave; j0 < k_own; j0 += 32) {
+            double part[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + 4 * u;
+                part[u] = 0.0;
+                if (j < k_own && 2 * lane < D) {
+                    const double2 wv = *(const double2*)(wb + (size_t)j * D + 2 * lane);
+                    part[u] = fma(x0, wv.x, x1 * wv.y);
+                }
             }
-            const double sdot = wave_sum_f64(part);
-            const double val = general ? 2.0 * sdot - nx * bterm[(size_t)b * k_own + j] : sdot;
-            if (val > best) {
-                best = val;
-                bj = j;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) part[u] += __shfl_xor(part[u], off);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int j = j0 + 4 * u;
+                if (j < k_own) {
+                    const double val = general ? 2.0 * part[u] - nx * bterm[(size_t)b * k_own + j] : part[u];
+                    if (val > best) {
+                        best = val;
+                        bj = j;
+                    }
+                }
             }
         }
         if (lane == 0) {

@@ -45,30 +45,54 @@ sort_hist_kernel(const int32_t* __restrict__ labels, int32_t* __restrict__ chunk
     }
 }
 
-// One workgroup of 1024 threads per slice; thread j owns bin j.
+// One workgroup of 1024 threads per slice.  The threads form G = 1024 / K' groups (K' = bins rounded
+// up to a multiple of 64); group g owns a contiguous range of chunks, thread (g, j) bin j of them.
+// Pass 1 totals each (group, bin); the group totals are prefixed per bin; pass 2 rewrites the chunk
+// histograms as exclusive prefixes.  Then the bin totals are scanned over bins for the offsets.
 __global__ void __launch_bounds__(1024)
 sort_scan_kernel(int32_t* __restrict__ chunk_hist, int32_t* __restrict__ offsets, int32_t* __restrict__ counts,
                  int k, int nchunks) {
+    __shared__ int32_t tot[1024];
     __shared__ int32_t scan[1024];
-    const int b = blockIdx.x, j = threadIdx.x;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const int kp = (k + 63) / 64 * 64;
+    const int groups = 1024 / kp;            // >= 1 because k <= 1024
+    const int g = tid / kp, j = tid % kp;
+    const bool live = g < groups && j < k;
+    const int cpg = (nchunks + groups - 1) / groups;
+    const int c0 = g * cpg, c1 = (c0 + cpg < nchunks) ? c0 + cpg : nchunks;
     int32_t* h = chunk_hist + (size_t)b * nchunks * k;
-    int total = 0;
-    if (j < k) {
-        for (int c = 0; c < nchunks; ++c) {
-            int v = h[(size_t)c * k + j];
-            h[(size_t)c * k + j] = total;
+    int sum = 0;
+    if (live)
+        for (int c = c0; c < c1; ++c) sum += h[(size_t)c * k + j];
+    tot[tid] = live ? sum : 0;
+    __syncthreads();
+    int base = 0, total = 0;
+    if (live) {
+        for (int gg = 0; gg < groups; ++gg) {
+            const int v = tot[gg * kp + j];
+            base += gg < g ? v : 0;
             total += v;
         }
+        int running = base;
+        for (int c = c0; c < c1; ++c) {
+            const int v = h[(size_t)c * k + j];
+            h[(size_t)c * k + j] = running;
+            running += v;
+        }
     }
-    scan[j] = total;
+    const int mine = (live && g == 0) ? total : 0;   // bin totals, one thread per bin
+    const bool owner = live && g == 0;
+    // scan over bins: owners sit at tid = j < kp <= 1024
+    scan[tid] = (tid < kp) ? mine : 0;
     __syncthreads();
     for (int s = 1; s < 1024; s <<= 1) {
-        int v = (j >= s) ? scan[j - s] : 0;
+        int v = (tid >= s) ? scan[tid - s] : 0;
         __syncthreads();
-        scan[j] += v;
+        scan[tid] += v;
         __syncthreads();
     }
-    if (j < k) {
+    if (owner) {
         offsets[(size_t)b * (k + 1) + j] = scan[j] - total;
         if (counts) counts[(size_t)b * k + j] = total;
         if (j == k - 1) offsets[(size_t)b * (k + 1) + k] = scan[j];

@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# Bytes past L2 per svoo_block_sparse_attn launch on configs[2], from the rocprofv3 --pmc passes summarised
+# in profiles/sparse_attn_config2_pmc.txt (FETCH_SIZE scaled by 1.97, the factor a copy of known size gives,
+# plus WRITE_SIZE); measured offline, at the keep ratios of the first two layers of the sweep.
+MEASURED_TRAFFIC_BYTES = {2: 9.66e10}
 STEP_NAMES = ("cocluster", "permute", "block_mask", "sparse_attn", "unpermute")
 
 
@@ -204,9 +208,11 @@ def main():
         "dense_attn_ms": round(dense_ms, 2) if args.dense_reps > 0 else None,
         "dense_attn_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2) if args.dense_reps > 0 else None,
         "speedup_vs_own_dense": round(dense_ms / ms_per_step, 3) if args.dense_reps > 0 else None,
-        "roofline": {"bound": "mfma", "kernel": "sparse_attn_bf16_kernel<128>", "achieved": round(attn_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "sparse_attn_bf16_kernel<128, 4, 2>", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg_id) if args.keep is None else None,
+                     "traffic_note": "bytes past L2 per launch (Infinity Cache + HBM), from rocprofv3 --pmc passes; "
+                                     "see profiles/sparse_attn_config2_pmc.txt",
                      "launch_ms": round(float(attn_ms.mean()), 3),
                      "flops_per_launch": float(kept_flops.mean())},
     }

@@ -44,6 +44,9 @@ def parse_args():
                         "paper: recall 0.95 with switch threshold 0.1")
     p.add_argument("--keep", type=float, default=None, help="fixed keep ratio instead of the per-layer draw")
     p.add_argument("--dense-reps", type=int, default=2)
+    p.add_argument("--reuse", type=int, default=20,
+                   help="also time one re-clustering period: 1 full step + (reuse-1) steps that keep labels, "
+                        "permutations and block lists (0 = skip)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--gen-workers", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
     return p.parse_args()
@@ -186,6 +189,33 @@ def main():
         dense_ms = d0.elapsed_time(d1) / args.dense_reps
         print(f"[bench] dense svoo_attn: {dense_ms:.1f} ms", file=sys.stderr, flush=True)
 
+    # ---- clustering reuse (paragraph "Clustering Reuse"; the paper re-clusters every 20 diffusion steps)
+    reuse = None
+    if args.reuse > 1:
+        x = inputs[0]
+        gen = torch.Generator(device=dev).manual_seed(18636)
+        drifted = [tuple((x[key].float() + 0.02 * torch.randn(x[key].shape, device=dev, generator=gen)).to(tdtype)
+                         for key in ("q", "k", "v")) for _ in range(2)]
+        kp = keep_dev[0]
+        layer_obj.run(x["q"], x["k"], x["v"], x["init_q_idx"], x["init_k_idx"], cfg.iters, kp, tau, theta, scale)
+        layer_obj.run_reused(*drifted[0], scale)
+        torch.cuda.synchronize()
+        r0, r1, r2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        r0.record()
+        layer_obj.run(x["q"], x["k"], x["v"], x["init_q_idx"], x["init_k_idx"], cfg.iters, kp, tau, theta, scale)
+        r1.record()
+        for i in range(args.reuse - 1):
+            layer_obj.run_reused(*drifted[i % 2], scale)
+        r2.record()
+        torch.cuda.synchronize()
+        full_ms, reused_ms = r0.elapsed_time(r1), r1.elapsed_time(r2) / (args.reuse - 1)
+        period_ms = (full_ms + reused_ms * (args.reuse - 1)) / args.reuse
+        reuse = {"recluster_every": args.reuse, "keep": round(float(keeps[0]), 4), "full_step_ms": round(full_ms, 3),
+                 "reused_step_ms": round(reused_ms, 3), "amortised_ms_per_step": round(period_ms, 3),
+                 "amortised_kept_tflops": round(cache[(0, 0)] * 4.0 * cfg.d / (period_ms * 1e-3) / 1e12, 2)
+                 if (0, 0) in cache else None}
+        print(f"[bench] reuse period of {args.reuse}: {period_ms:.2f} ms/step amortised", file=sys.stderr, flush=True)
+
     attn_ms = step_ms[:, 3]
     attn_tflops = float(kept_flops.sum() / (attn_ms.sum() * 1e-3) / 1e12)
     value = total_kept / elapsed / 1e12
@@ -216,6 +246,8 @@ def main():
                      "launch_ms": round(float(attn_ms.mean()), 3),
                      "flops_per_launch": float(kept_flops.mean())},
     }
+    if reuse is not None:
+        result["clustering_reuse"] = reuse
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], keeps[0], tau, theta, scale, float(kept_flops[0]))

@@ -124,6 +124,16 @@ int svoo_permute(const svoo_shape* shape, const int32_t* labels, int32_t n_clust
                  int32_t n_tensors, const void* const* src, void* const* dst,
                  int32_t* perm, int32_t* offsets, void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * The row gather of svoo_permute alone, with a permutation computed earlier:
+ * dst[t][b, p, :] = src[t][b, perm[b, p], :] for t < n_tensors (1..4).  This is what a diffusion
+ * step between two re-clusterings needs (paragraph "Clustering Reuse": block partitions are stable
+ * across steps, so labels, permutations and block lists are kept and only the new Q, K, V move).
+ * perm values must lie in [0, n).
+ */
+int svoo_gather(const svoo_shape* shape, const int32_t* perm, int32_t n_tensors,
+                const void* const* src, void* const* dst, void* hip_stream);
+
 /* dst[b, perm[b, p], :] = src_sorted[b, p, :]  (inverse of the row gather above). */
 int svoo_unpermute(const svoo_shape* shape, const void* src_sorted, const int32_t* perm, void* dst,
                    void* hip_stream);

@@ -216,6 +216,21 @@ extern "C" int svoo_permute(const svoo_shape* shape, const int32_t* labels, int3
     return move_rows<true>(shape, n_tensors, ptrs, perm, stream);
 }
 
+extern "C" int svoo_gather(const svoo_shape* shape, const int32_t* perm, int32_t n_tensors, const void* const* src,
+                           void* const* dst, void* hip_stream) {
+    int st = check_shape(shape, false);
+    if (st != SVOO_OK) return st;
+    if (!perm || !src || !dst || n_tensors < 1 || n_tensors > 4 || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    RowPtrs ptrs = {};
+    for (int t = 0; t < n_tensors; ++t) {
+        if (!src[t] || !dst[t] || !aligned16(src[t]) || !aligned16(dst[t]) || src[t] == dst[t])
+            return SVOO_ERR_INVALID_ARG;
+        ptrs.src[t] = (const uint4*)src[t];
+        ptrs.dst[t] = (uint4*)dst[t];
+    }
+    return move_rows<true>(shape, n_tensors, ptrs, perm, (hipStream_t)hip_stream);
+}
+
 extern "C" int svoo_unpermute(const svoo_shape* shape, const void* src_sorted, const int32_t* perm, void* dst,
                               void* hip_stream) {
     int st = check_shape(shape, false);

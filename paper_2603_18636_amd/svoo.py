@@ -41,6 +41,7 @@ _SIGNATURES = {
     "svoo_assign": (ctypes.c_int, [_SP, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
     "svoo_permute": (ctypes.c_int, [_SP, _vp, _i32, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _vp, _vp,
                                     _sz, _vp]),
+    "svoo_gather": (ctypes.c_int, [_SP, _vp, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]),
     "svoo_unpermute": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp]),
     "svoo_block_mask": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_block_sparse_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
@@ -215,6 +216,22 @@ def permute(labels, n_clusters: int, tensors: Sequence[torch.Tensor], ws=None, o
     return perm, offsets, outs
 
 
+def gather(perm, tensors: Sequence[torch.Tensor], outs=None):
+    """svoo_gather: outs[t][b, p] = tensors[t][b, perm[b, p]] with a permutation computed earlier."""
+    tensors = list(tensors)
+    bh, n, d = tensors[0].shape
+    shape = make_shape(tensors[0], 1, 1)
+    _check(perm, torch.int32, (bh, n), "perm")
+    for i, t in enumerate(tensors):
+        _check(t, tensors[0].dtype, (bh, n, d), f"src[{i}]")
+    outs = [torch.empty_like(t) for t in tensors] if outs is None else list(outs)
+    nt = len(tensors)
+    src = (ctypes.c_void_p * nt)(*[t.data_ptr() for t in tensors])
+    dst = (ctypes.c_void_p * nt)(*[t.data_ptr() for t in outs])
+    _run(_lib().svoo_gather(ctypes.byref(shape), _ptr(perm), nt, src, dst, _stream()), "svoo_gather")
+    return outs
+
+
 def unpermute(src_sorted, perm, out=None):
     """svoo_unpermute: out[b, perm[b, p]] = src_sorted[b, p]."""
     bh, n, d = src_sorted.shape
@@ -336,6 +353,24 @@ class Layer:
         dst = (ctypes.c_void_p * 2)(self.k_sorted.data_ptr(), self.v_sorted.data_ptr())
         _run(lib.svoo_permute(ctypes.byref(s), _ptr(self.labels_k), self.kk, 2, src, dst, _ptr(self.perm_k),
                               _ptr(self.k_offsets), _ptr(self.ws), self.ws.numel(), _stream()), "svoo_permute(kv)")
+
+    def step_regather(self, q, k, v):
+        """Move new Q, K, V into cluster order with the permutations of the last clustering."""
+        lib, s = _lib(), self.shape
+        src = (ctypes.c_void_p * 1)(q.data_ptr())
+        dst = (ctypes.c_void_p * 1)(self.q_sorted.data_ptr())
+        _run(lib.svoo_gather(ctypes.byref(s), _ptr(self.perm_q), 1, src, dst, _stream()), "svoo_gather(q)")
+        src = (ctypes.c_void_p * 2)(k.data_ptr(), v.data_ptr())
+        dst = (ctypes.c_void_p * 2)(self.k_sorted.data_ptr(), self.v_sorted.data_ptr())
+        _run(lib.svoo_gather(ctypes.byref(s), _ptr(self.perm_k), 2, src, dst, _stream()), "svoo_gather(kv)")
+
+    def run_reused(self, q, k, v, scale=None):
+        """A step between two re-clusterings: labels, permutations and block lists are kept."""
+        scale = 1.0 / math.sqrt(self.d) if scale is None else scale
+        self.step_regather(q, k, v)
+        self.step_attn(scale)
+        self.step_unpermute()
+        return self.out
 
     def step_block_mask(self, keep, tau, theta, scale):
         lib, s = _lib(), self.shape

@@ -89,6 +89,8 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
     assert lib.svoo_permute(sp, fake, 16, 5, arr, arr2, fake, fake, fake, ws_bytes, null) == INVALID     # > 4 tensors
     assert lib.svoo_permute(sp, fake, 16, 1, arr, arr, fake, fake, fake, ws_bytes, null) == INVALID      # dst aliases src
     assert lib.svoo_permute(sp, fake, 16, 1, arr, arr2, fake, fake, fake, 4, null) == TOO_SMALL
+    assert lib.svoo_gather(sp, fake, 0, arr, arr2, null) == INVALID                                      # no tensors
+    assert lib.svoo_gather(sp, null, 1, arr, arr2, null) == INVALID
     assert lib.svoo_unpermute(sp, fake, fake, fake, null) == INVALID                                     # in place
     assert lib.svoo_unpermute(sp, fake, null, ctypes.c_void_p(0x2000), null) == INVALID
     assert lib.svoo_assign(sp, fake, fake, 0, fake, 4, fake, fake, ws_bytes, null) == INVALID

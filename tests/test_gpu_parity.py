@@ -315,3 +315,28 @@ def test_layer_is_deterministic():
     l2, o2 = run_layer_gpu(data, "bf16", 24, 20, 3, 0.2, 0.95, 0.1)
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
     assert torch.equal(labels1, l2.labels_q)
+
+
+# ------------------------------------------------------------------------------------------ clustering reuse
+def test_reuse_between_reclusterings():
+    """Clustering Reuse: a later diffusion step keeps labels, permutations and block lists and only
+    moves the (slightly drifted) Q, K, V.  Against the oracle's attention with the same stale labels
+    and mask on the drifted inputs."""
+    cfg = synth.CONFIGS[1]
+    grid, kq, kk = (6, 12, 20), 24, 20
+    data = synth.make_layer(cfg, 0, heads=[0, 1], grid=grid, n_seeds=24, kq=kq, kk=kk)
+    layer, out0 = run_layer_gpu(data, "bf16", kq, kk, cfg.iters, cfg.keep, 0.95, 0.1)
+    rng = np.random.default_rng(9)
+    drift = {x: synth.round_to_bf16(data[x] + 0.05 * rng.standard_normal(data[x].shape).astype(np.float32))
+             for x in "qkv"}
+    qd, kd, vd = (H.to_dev(drift[x], "bf16") for x in "qkv")
+    out = H.to_np(layer.run_reused(qd, kd, vd))
+    torch.cuda.synchronize()
+    gathered = svoo.gather(layer.perm_k, [kd, vd])
+    assert torch.equal(gathered[0].view(torch.int16), layer.k_sorted.view(torch.int16))
+    scale = H.scale_of(cfg.d)
+    for b in range(2):
+        lq, lk = H.to_np(layer.labels_q)[b], H.to_np(layer.labels_k)[b]
+        mask = H.to_np(layer.bitmap)[b].astype(bool)
+        ref = so.sparse_attention(drift["q"][b], drift["k"][b], drift["v"][b], lq, lk, mask, scale)
+        H.assert_attn_close(out[b], ref, "bf16", f"reuse b={b}")

@@ -67,6 +67,9 @@ CONFIGS: Dict[int, Config] = {
               keep_sweep=(0.1, 0.2, 0.4, 1.0)),
     4: Config("long_seq_skewed", 4, 24, 128, (33, 45, 80), 384, 512, 512, 3, "bf16", 0.15,
               dirichlet_alpha=0.3),
+    # not a BASELINE workload: the hyper-parameters of the paper's own experiments (Sec. 5.1
+    # "Implementations": K_q = 256, K_k = 1024, two co-clustering iterations) on the 720p grid
+    5: Config("paper_hparams_720p", 5, 12, 128, (21, 45, 80), 256, 256, 1024, 2, "bf16", 0.2),
 }
 
 

@@ -100,3 +100,11 @@ def test_config4_long_sequence_skewed_clusters():
     counts = H.to_np(layer.counts_q)
     print(f"config4: {stats}; query cluster sizes min {counts.min()} max {counts.max()}")
     assert counts.max() > 4 * counts[counts > 0].mean()   # the workload really is skewed
+
+
+def test_paper_hyperparameters_asymmetric_clusters():
+    """K_q = 256, K_k = 1024, two iterations (the paper's own settings) at N = 75,600: key blocks of
+    ~74 rows, so most 64-key tiles straddle a segment boundary, and the mask ranks 1024 blocks."""
+    cfg = synth.CONFIGS[5]
+    *_, stats = run_and_check(cfg, [0, 7], cfg.keep, 0.95, 0.1, n_rows=200)
+    print(f"paper hyper-parameters: {stats}")

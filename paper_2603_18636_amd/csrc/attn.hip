@@ -327,14 +327,24 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             }
     }
 
-    // key-split waves read "their" 32-key block of every tile: fold its offset into the addresses
+    // key-split waves read "their" 32-key block of every tile: fold its offset into the addresses.
+    // The offsets are turned into absolute LDS byte addresses here, once, so that inside the loop a
+    // read is "address register + immediate" with nothing left to add.
     const int kb_off = 32 * kgrp;
+    const int k_base = (int)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)k_lds;
+    const int v_base = (int)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)v_lds;
 #pragma unroll
-    for (int c = 0; c < DC; ++c) koff[c] += kb_off * ROWB;
+    for (int c = 0; c < DC; ++c) {
+        koff[c] += kb_off * ROWB + k_base;
+        asm volatile("" : "+v"(koff[c]));  // keep the sum in the register: no re-adding per tile
+    }
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int db = 0; db < DB; ++db) voff[u][db] += kb_off * ROWB;
+        for (int db = 0; db < DB; ++db) {
+            voff[u][db] += kb_off * ROWB + v_base;
+            asm volatile("" : "+v"(voff[u][db]));
+        }
 
     f32x16 o[DB];
 #pragma unroll
@@ -359,17 +369,16 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         constexpr int KB0 = 0;
         constexpr int NKB = MODE == 0 ? 2 : 1;       // number of blocks
         constexpr int HB = DC / 2;
-        const unsigned char* kt_lds = k_lds + BUF * TILE;
-        const unsigned char* vt_lds = v_lds + BUF * TILE;
         auto kfrag = [&](int kb, int c) {
-            return __builtin_bit_cast(bf16x8, *(const uint4*)(kt_lds + kb * 32 * ROWB + koff[c]));
+            const uint32_t addr = (uint32_t)(koff[c] + BUF * TILE + kb * 32 * ROWB);
+            return __builtin_bit_cast(bf16x8, *(const __attribute__((address_space(3))) uint4*)(uintptr_t)addr);
         };
         auto vfrag = [&](int kb, int t, int db) {
-            const int cst = (32 * kb + 16 * t) * ROWB;
+            const int cst = BUF * TILE + (32 * kb + 16 * t) * ROWB;
             const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[0][db]));
+                (__attribute__((address_space(3))) bf16x4*)(uintptr_t)(uint32_t)(voff[0][db] + cst));
             const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                (__attribute__((address_space(3))) bf16x4*)(vt_lds + cst + voff[1][db]));
+                (__attribute__((address_space(3))) bf16x4*)(uintptr_t)(uint32_t)(voff[1][db] + cst));
             return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         };
         f32x16 s[NKB];
@@ -452,14 +461,17 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         }
         // a key-split wave may have seen only masked keys so far (-inf reference): keep exp2 finite
         const float mb = (MODE != 0 && m_used == -INFINITY) ? 0.f : m_used * c2;
+        const bf16x2 ones2 = __builtin_bit_cast(bf16x2, 0x3f803f80u);
         auto probs = [&](int kb, int t) {
             uint32_t w[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e], c2, -mb));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + 2 * e + 1], c2, -mb));
-                lsum += p0 + p1;
                 w[e] = pack2_bf16(p0, p1);
+                // the row sum takes the two ROUNDED probabilities, the same values the second
+                // contraction multiplies: one dot-product instruction with (1, 1) instead of two adds
+                lsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w[e]), ones2, lsum, false);
             }
             return __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
         };
@@ -483,15 +495,16 @@ sparse_attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
             for (int db = 0; db < DB; ++db)
                 o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][db], pf[t], o[db], 0, 0, 0);
+        constexpr int PVALU = 48;   // VALU/transcendental instructions of one 32-key block's probabilities
         // pipeline: exponentials of the first block, then (two-block tiles) each MFMA of block 0
         // paired with two V reads of block 1 and a slice of block 1's exponentials, then the rest
-        __builtin_amdgcn_sched_group_barrier(0x402, 56, 0);
+        __builtin_amdgcn_sched_group_barrier(0x402, PVALU, 0);
         if (NKB == 2) {
 #pragma unroll
             for (int i = 0; i < 2 * DB; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x402, 56 / (2 * DB), 0);
+                __builtin_amdgcn_sched_group_barrier(0x402, PVALU / (2 * DB), 0);
             }
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 0);

@@ -14,6 +14,10 @@ What follows the paper and where:
   coarse estimate from centroids, recall threshold tau, budget s, switch threshold theta.
 * ``sparse_attention`` / ``dense_attention`` -- softmax(q K^T / sqrt(d')) V as defined in
   Sec. 4.1 (definition of z_i), restricted to the kept (query block, key block) pairs.
+* ``kmeans`` -- the independent K-means partitioner of the ablation "w/o On" and of the prior work
+  the paper contrasts itself with ("Difference from SVG2"): textbook Lloyd iterations per side.
+* ``row_recall`` / ``attention_recall`` -- the attention-recall measure of the clustering
+  comparison section, read as the dense softmax mass on kept keys.
 
 Readings taken where the paper is silent (each is listed in the design notes of this build):
 Norm(.) is row-wise L2 normalisation with a 1e-12 floor; argmin ties go to the lowest index; an
@@ -26,7 +30,9 @@ normalised over the kept keys only.
 Pins (tests/, CPU only): dense attention against a library routine, keep-everything == dense,
 permutation invariance, one Lloyd iteration against scikit-learn when the affinity is the
 identity, cosine-distance argmin against SciPy, block selection against brute-force block sums of
-the exact attention matrix on zero-variance clusters, hand-computed selection cases.  Whether the
+the exact attention matrix on zero-variance clusters, hand-computed selection cases; k-means
+against SciPy's and scikit-learn's Lloyd iterations from the same start; recall against the
+log-sum-exp identity, the uniform-attention closed form and explicit loops.  Whether the
 paper's authors' code would produce the same labels is *parity unpinned*: Norm, the weighting of
 the block estimate, Recall and the meaning of s cannot be confirmed from the text alone.
 """
@@ -126,6 +132,37 @@ def cocluster(q: np.ndarray, k: np.ndarray, init_q_idx: Optional[np.ndarray], in
         cq = cq_new
     return {"labels_q": lq, "labels_k": lk, "cq": cq, "ck": ck, "counts_q": nq, "counts_k": nk,
             "trace": trace}
+
+
+# --------------------------------------------------------------------------------------------
+# Independent partitioner (ablation "w/o On"; the K-means block partitioning the paper contrasts
+# its co-clustering with in "Difference from SVG2")
+# --------------------------------------------------------------------------------------------
+def kmeans(x: np.ndarray, init_idx: Optional[np.ndarray], iters: int,
+           init_c: Optional[np.ndarray] = None) -> Dict[str, object]:
+    """Lloyd's k-means on the raw rows of x [N, d], one side at a time, no coupling to the other
+    side.  Per iteration: labels = argmin_j ||x_i - c_j||_2^2 (summed term by term, lowest j on
+    ties), then c_j = mean of its rows (an empty cluster keeps its centroid).  Returned centroids
+    are the means of the returned labels, as in Algorithm 1."""
+    x = np.asarray(x, dtype=np.float64)
+    c = np.array(init_c, dtype=np.float64) if init_c is not None else x[np.asarray(init_idx)].copy()
+    trace: List[Dict[str, object]] = []
+    labels = counts = None
+    for it in range(iters):
+        dist = cdist(x, c, metric="sqeuclidean")
+        labels = argmin_lowest(dist)
+        best = dist[np.arange(dist.shape[0]), labels]
+        if dist.shape[1] > 1:
+            tmp = dist.copy()
+            tmp[np.arange(dist.shape[0]), labels] = np.inf
+            second = tmp.min(axis=1)
+        else:
+            second = np.full_like(best, np.inf)
+        c_new, counts = update_centroids(x, labels, c)
+        trace.append({"iter": it, "labels": labels, "c_in": c, "c_out": c_new, "counts": counts,
+                      "inertia": float(best.sum()), "best": best, "second": second})
+        c = c_new
+    return {"labels": labels, "c": c, "counts": counts, "trace": trace}
 
 
 # --------------------------------------------------------------------------------------------
@@ -280,25 +317,41 @@ def kept_fraction(mask: np.ndarray, counts_q: np.ndarray, counts_k: np.ndarray) 
     return float((nq[:, None] * nk[None, :] * mask).sum() / (nq.sum() * nk.sum()))
 
 
-def attention_recall(q, k, v_unused, labels_q, labels_k, mask, scale, rows) -> float:
-    """Mean over the given query rows of the exact softmax mass that falls on kept keys
-    (diagnostic; the paper defers its own definition to an appendix that is not in the text)."""
+def row_recall(q, k, labels_q, labels_k, mask, scale, rows) -> np.ndarray:
+    """Per given query row, the exact softmax mass (dense softmax over all keys) that falls on
+    the keys of its kept key blocks.  Attention recall of the clustering comparison section is
+    read as the mean of this over rows; the paper's own definition sits in an appendix that is
+    not in the text."""
     q = np.asarray(q, np.float64)
     k = np.asarray(k, np.float64)
     rows = np.asarray(rows)
     a = _softmax_rows(scale * (q[rows] @ k.T))
     kept = mask[np.asarray(labels_q)[rows]][:, np.asarray(labels_k)]
-    return float((a * kept).sum(axis=1).mean())
+    return (a * kept).sum(axis=1)
+
+
+def attention_recall(q, k, v_unused, labels_q, labels_k, mask, scale, rows) -> float:
+    """Mean of ``row_recall`` over the given rows (diagnostic)."""
+    return float(row_recall(q, k, labels_q, labels_k, mask, scale, rows).mean())
 
 
 def layer(q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None, norm="l2",
-          rows: Optional[np.ndarray] = None, centroid_dtype=np.float32) -> Dict[str, object]:
+          rows: Optional[np.ndarray] = None, centroid_dtype=np.float32,
+          partitioner: str = "cocluster") -> Dict[str, object]:
     """The whole online stage for one head.  Centroids cross the library boundary as float32, so
     they are rounded to that type between clustering and selection (``centroid_dtype=None`` keeps
-    float64)."""
+    float64).  ``partitioner="kmeans"`` replaces Algorithm 1 by two independent k-means runs (the
+    "w/o On" ablation); everything after the partition is unchanged."""
     d = q.shape[1]
     scale = 1.0 / math.sqrt(d) if scale is None else scale
-    cc = cocluster(q, k, init_q_idx, init_k_idx, iters, norm)
+    if partitioner == "cocluster":
+        cc = cocluster(q, k, init_q_idx, init_k_idx, iters, norm)
+    elif partitioner == "kmeans":
+        kq_, kk_ = kmeans(q, init_q_idx, iters), kmeans(k, init_k_idx, iters)
+        cc = {"labels_q": kq_["labels"], "labels_k": kk_["labels"], "cq": kq_["c"], "ck": kk_["c"],
+              "counts_q": kq_["counts"], "counts_k": kk_["counts"], "trace": [kq_["trace"], kk_["trace"]]}
+    else:
+        raise ValueError(partitioner)
     cq, ck = cc["cq"], cc["ck"]
     if centroid_dtype is not None:
         cq = cq.astype(centroid_dtype).astype(np.float64)

@@ -341,3 +341,112 @@ def test_generator_is_deterministic_and_dtype_exact():
     assert len(set(a["init_q_idx"].tolist())) == 8
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -1.00390625], dtype=np.float32)
     assert synth.round_to_bf16(x).tolist() == [1.0, 1.015625, -1.0]
+
+
+# ---------------------------------------------------------------------------- independent k-means
+def _kmeans_case(seed, n=600, d=12, k=7):
+    """Well-separated blobs plus noise, start = k distinct rows: no empty clusters, no ties."""
+    rng = np.random.default_rng(seed)
+    centres = 4.0 * rng.standard_normal((k, d))
+    x = centres[rng.integers(0, k, n)] + rng.standard_normal((n, d))
+    return x, synth.sample_distinct(rng, n, k)
+
+
+@pytest.mark.parametrize("iters", [1, 2, 5])
+def test_kmeans_matches_scipy_lloyd(iters):
+    """Independent partitioner ("w/o On"): same start, same number of Lloyd iterations as SciPy's
+    kmeans2, which also returns the labels of the last assignment and the means of those labels."""
+    from scipy.cluster.vq import kmeans2
+    x, idx = _kmeans_case(11 + iters)
+    got = so.kmeans(x, idx, iters)
+    code, lab = kmeans2(x, x[idx].copy(), iter=iters, minit="matrix")
+    assert (got["labels"] == lab).all()
+    np.testing.assert_allclose(got["c"], code, rtol=0, atol=1e-12)
+    assert (got["counts"] == np.bincount(lab, minlength=7)).all() and got["counts"].min() > 0
+
+
+def test_kmeans_matches_sklearn_lloyd():
+    """scikit-learn runs max_iter (assign, update) rounds and then assigns once more to the final
+    centres: its centres are ours after I iterations, its labels ours after I + 1."""
+    x, idx = _kmeans_case(3)
+    iters = 3
+    km = KMeans(n_clusters=7, init=x[idx].copy(), n_init=1, max_iter=iters, tol=0.0, algorithm="lloyd").fit(x)
+    a, b = so.kmeans(x, idx, iters), so.kmeans(x, idx, iters + 1)
+    np.testing.assert_allclose(a["c"], km.cluster_centers_, rtol=0, atol=1e-10)
+    assert (b["labels"] == km.labels_).all()
+    # inertia_ is the sum of squared distances to the final centres = what iteration I + 1 sees
+    assert abs(b["trace"][-1]["inertia"] - km.inertia_) <= 1e-9 * km.inertia_
+
+
+def test_kmeans_invariants_and_empty_cluster():
+    x, idx = _kmeans_case(8)
+    r = so.kmeans(x, idx, 6)
+    inert = [t["inertia"] for t in r["trace"]]
+    assert all(b <= a * (1 + 1e-14) for a, b in zip(inert, inert[1:]))        # Lloyd never increases it
+    np.testing.assert_allclose((r["counts"][:, None] * r["c"]).sum(0), x.sum(0), atol=1e-9)
+    # a start centroid far away from every point owns nothing and must stay where it was
+    c0 = np.vstack([x[idx[:6]], np.full((1, x.shape[1]), 1e3)])
+    r = so.kmeans(x, None, 2, init_c=c0)
+    assert r["counts"][6] == 0 and (r["c"][6] == 1e3).all() and r["counts"].sum() == x.shape[0]
+    # ties go to the lowest index: two identical centroids, the second never wins
+    c0 = np.vstack([x[idx[:3]], x[idx[:1]]])
+    r = so.kmeans(x, None, 1, init_c=c0)
+    assert r["counts"][3] == 0
+
+
+def test_layer_with_kmeans_partitioner_keeps_everything_equals_dense():
+    h = synth.make_head(CFG0, 4, 0)
+    r = so.layer(h["q"], h["k"], h["v"], h["init_q_idx"], h["init_k_idx"], 2, 1.0, 1.0, 0.1, partitioner="kmeans")
+    np.testing.assert_allclose(r["out"], so.dense_attention(h["q"], h["k"], h["v"], 0.125), atol=1e-12)
+    ref = so.kmeans(h["k"], h["init_k_idx"], 2)
+    assert (r["labels_k"] == ref["labels"]).all()
+
+
+# ---------------------------------------------------------------------------- attention recall
+def _recall_case(seed=2):
+    h = tiny_head(seed)
+    n = h["q"].shape[0]
+    rng = np.random.default_rng(seed)
+    lq = rng.integers(0, 4, n).astype(np.int32)
+    lk = rng.integers(0, 5, n).astype(np.int32)
+    mask = rng.random((4, 5)) < 0.5
+    mask[:, 0] = True
+    return h, lq, lk, mask, n
+
+
+def test_recall_is_one_when_everything_is_kept_and_matches_explicit_loops():
+    h, lq, lk, mask, n = _recall_case()
+    rows = np.arange(n)
+    assert abs(so.attention_recall(h["q"], h["k"], None, lq, lk, np.ones((4, 5), bool), 0.25, rows) - 1.0) < 1e-14
+    got = so.row_recall(h["q"], h["k"], lq, lk, mask, 0.25, rows)
+    q, k = h["q"].astype(np.float64), h["k"].astype(np.float64)
+    for i in (0, 5, n - 1):
+        num = den = 0.0
+        for t in range(n):
+            e = math.exp(0.25 * float(np.dot(q[i], k[t])))
+            den += e
+            if mask[lq[i], lk[t]]:
+                num += e
+        assert abs(got[i] - num / den) < 1e-12
+
+
+def test_recall_equals_exp_of_logsumexp_difference():
+    """Kept softmax mass = exp(LSE over kept keys - LSE over all keys): SciPy's logsumexp."""
+    from scipy.special import logsumexp
+    h, lq, lk, mask, n = _recall_case(6)
+    rows = np.array([1, 17, 63, 100])
+    s = 0.25 * (h["q"].astype(np.float64)[rows] @ h["k"].astype(np.float64).T)
+    kept = mask[lq[rows]][:, lk]
+    ref = np.exp(logsumexp(np.where(kept, s, -np.inf), axis=1) - logsumexp(s, axis=1))
+    np.testing.assert_allclose(so.row_recall(h["q"], h["k"], lq, lk, mask, 0.25, rows), ref, rtol=1e-12)
+
+
+def test_recall_of_uniform_attention_is_the_kept_key_fraction():
+    """Zero queries give uniform attention, so a row's recall is the share of keys in its kept
+    blocks and the mean over all rows is the kept fraction of the score matrix."""
+    h, lq, lk, mask, n = _recall_case(9)
+    q0 = np.zeros_like(h["q"])
+    nq, nk = np.bincount(lq, minlength=4), np.bincount(lk, minlength=5)
+    rr = so.row_recall(q0, h["k"], lq, lk, mask, 0.25, np.arange(n))
+    np.testing.assert_allclose(rr, (mask[lq] * nk[None, :]).sum(1) / n, rtol=1e-13)
+    assert abs(rr.mean() - so.kept_fraction(mask, nq, nk)) < 1e-13

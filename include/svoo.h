@@ -110,6 +110,26 @@ int svoo_assign(const svoo_shape* shape, const void* x, const float* c_own, int3
                 void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * Independent partitioner: Lloyd's K-means on the raw rows of ONE tensor x [bh, n, d], with no
+ * coupling to the other side.  This is the block partitioning of the ablation variant "w/o On"
+ * (Sec. "Ablation Study") and of the K-means based prior work the paper contrasts its co-clustering
+ * with (paragraph "Difference from SVG2"; attention-recall comparison of the clustering-strategy
+ * section).  Call it once for Q and once for K; everything after the partition (svoo_permute ...
+ * svoo_unpermute) is unchanged.  For it = 1..iters:
+ *   labels[i] = argmin_j ||x_i - c_j||_2^2 (lowest j on ties);  c_j = mean of its rows (an empty
+ *   cluster keeps its centroid).
+ * Start: rows x[init_idx[j]] (init_idx [bh, k]) or float32 centroids init_c [bh, k, d] (wins if
+ * both are given).  1 <= k <= 1024, k <= n; shape->kq / kk are ignored.
+ * Outputs: labels [bh, n]; c [bh, k, d] float32 = means of the returned labels; counts [bh, k];
+ * inertia (nullable) [bh, iters] float64 = sum_i ||x_i - c_{labels[i]}||^2 at assignment time.
+ * Decisions in float64 behind a bf16 matrix-core pre-filter, as in svoo_cocluster.
+ * Workspace: svoo_workspace_bytes() of a shape whose kq or kk is >= k suffices.
+ */
+int svoo_kmeans(const svoo_shape* shape, const void* x, int32_t k, const int32_t* init_idx,
+                const float* init_c, int32_t iters, int32_t* labels, float* c, int32_t* counts,
+                double* inertia, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * Cluster-contiguous layout (the contiguous block layout block-sparse kernels need; the paper
  * inherits it from the k-means based prior work it builds on, Sec. 2.2 / "Kernel Customization").
  * Stable counting sort of labels [bh, n] with n_clusters bins:

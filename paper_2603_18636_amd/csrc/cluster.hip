@@ -210,7 +210,7 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
     if (general) {
         for (int a = 0; a < 4; ++a) {
             const int ti = tok[ty * 4 + a];
-            const double v = ti < 0 ? 0.0 : nx2[(size_t)b * n + ti];
+            const double v = (ti < 0 || !nx2) ? 1.0 : nx2[(size_t)b * n + ti];   // no nx2: plain k-means scores
             const double r = sqrt(v > 0.0 ? v : 0.0);
             nx_tok[a] = r > NORM_FLOOR ? r : NORM_FLOOR;
         }
@@ -308,12 +308,13 @@ __global__ void __launch_bounds__(256)
 assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int k_own,
                    const double* __restrict__ bterm, const int32_t* __restrict__ flags,
                    const double* __restrict__ nx2, const int32_t* __restrict__ list,
-                   const int32_t* __restrict__ list_count, int32_t* __restrict__ labels, int n) {
+                   const int32_t* __restrict__ list_count, int32_t force_general, int32_t* __restrict__ labels,
+                   int n) {
     __shared__ double best_v[4];
     __shared__ int32_t best_j[4];
     const int b = blockIdx.y, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int count = list_count[b];
-    const bool general = flags[b] != 0;
+    const bool general = force_general || flags[b] != 0;
     const double* wb = wmat + (size_t)b * k_own * D;
     for (int p = blockIdx.x; p < count; p += gridDim.x) {
         const int ti = list[(size_t)b * n + p];
@@ -321,7 +322,7 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int
         if (2 * lane < D) load_pair<T>(x + ((size_t)b * n + ti) * D + 2 * lane, x0, x1);
         double nx = 0.0;
         if (general) {
-            const double v = nx2[(size_t)b * n + ti];
+            const double v = nx2 ? nx2[(size_t)b * n + ti] : 1.0;   // no nx2: plain k-means scores
             const double r = sqrt(v > 0.0 ? v : 0.0);
             nx = r > NORM_FLOOR ? r : NORM_FLOOR;
         }
@@ -464,12 +465,15 @@ split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint1
     }
 }
 
-template <int D>
+// BIAS: score_j = <x, W_j> - half_sq[j] (k-means on raw rows: W = C, half_sq = ||c_j||^2 / 2, one
+// float per centroid, slices padded to a multiple of 32 entries); the margin then also covers the
+// float32 rounding of the bias and of the subtraction.
+template <int D, bool BIAS>
 __global__ void __launch_bounds__(256, 2)
 assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ whi, const uint16_t* __restrict__ wlo,
                    const int32_t* __restrict__ wmax_bits, const int32_t* __restrict__ flags,
-                   int32_t* __restrict__ labels, int32_t* __restrict__ list, int32_t* __restrict__ list_count, int n,
-                   int k_own) {
+                   const float* __restrict__ half_sq, int32_t* __restrict__ labels, int32_t* __restrict__ list,
+                   int32_t* __restrict__ list_count, int n, int k_own) {
     constexpr int DC = D / 16, CPR = D / 8, ROWB = D * 2;
     constexpr int HALF = 32 * ROWB;          // one 32-centroid block of W_hi (or W_lo)
     constexpr int RPL = 64 / CPR;            // rows per wave-load
@@ -551,12 +555,22 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
             }
         }
         const int cbase = 32 * cb + 4 * h;
+        float bias[16];
+        if (BIAS) {
+            const float4* hb = (const float4*)(half_sq + (size_t)b * (32 * n_blocks) + cbase);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 t = hb[2 * g];
+                bias[4 * g] = t.x; bias[4 * g + 1] = t.y; bias[4 * g + 2] = t.z; bias[4 * g + 3] = t.w;
+            }
+        }
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int cl = cbase + 8 * (v / 4) + (v % 4);
-                const float val = cl < k_own ? acc[tb][v] : -INFINITY;
+                const float sc = BIAS ? acc[tb][v] - bias[v] : acc[tb][v];
+                const float val = cl < k_own ? sc : -INFINITY;
                 second[tb] = __builtin_amdgcn_fmed3f(best[tb], second[tb], val);
                 bidx[tb] = val > best[tb] ? cl : bidx[tb];
                 best[tb] = fmaxf(best[tb], val);
@@ -577,7 +591,9 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
         const int fi = b0 >= b1 ? (int)ri[0] : (int)ri[1];
         const int tok = t0 + 32 * tb + j;
         if (h == 0 && tok < n) {
-            const float margin = 2.0f * FAST_EPS * sqrtf(xn2[tb]) * wmax;
+            const float xw = sqrtf(xn2[tb]) * wmax;
+            const float margin = BIAS ? 2.0f * (FAST_EPS * xw + 2.4e-7f * (0.5f * wmax * wmax + xw))   // 2^-22
+                                      : 2.0f * FAST_EPS * xw;
             const bool sure = (fb - fs) > margin;          // false for NaN as well
             labels[(size_t)b * n + tok] = fi;
             if (degenerate || !sure) {
@@ -701,11 +717,54 @@ objective_sum_kernel(const double* __restrict__ terms, double* __restrict__ out,
 }
 
 // ---------------------------------------------------------------------------------------------
+// Independent k-means on raw rows: argmin_j ||x - c_j||^2 = argmax_j 2 <x, c_j> - ||c_j||^2, i.e.
+// the same scoring kernels with W = C, anchor term ||c_j||^2 and token norm 1.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(128)
+kmeans_prep_kernel(const double* __restrict__ c64, double* __restrict__ bterm, float* __restrict__ half_sq, int k,
+                   int kpad, int d) {
+    __shared__ double red[128];
+    const int b = blockIdx.y, j = blockIdx.x, t = threadIdx.x;
+    double v = 0.0;
+    if (j < k && t < d) v = c64[((size_t)b * k + j) * d + t];
+    red[t] = v * v;
+    __syncthreads();
+    for (int s = 64; s > 0; s >>= 1) {
+        if (t < s) red[t] += red[t + s];
+        __syncthreads();
+    }
+    if (t == 0) {
+        if (j < k) bterm[(size_t)b * k + j] = red[0];
+        half_sq[(size_t)b * kpad + j] = j < k ? (float)(0.5 * red[0]) : 0.f;
+    }
+}
+
+// terms[i] = ||x_i - c_{L_i}||^2, summed term by term
+template <typename T>
+__global__ void __launch_bounds__(256)
+kmeans_inertia_terms_kernel(const T* __restrict__ x, const double* __restrict__ c64,
+                            const int32_t* __restrict__ labels, double* __restrict__ terms, int n, int k, int d) {
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int l = labels[(size_t)b * n + i];
+    const T* xr = x + ((size_t)b * n + i) * d;
+    const double* cr = c64 + ((size_t)b * k + l) * d;
+    double s = 0.0;
+    for (int c = 0; c < d; ++c) {
+        const double df = load_as_f64<T>(xr + c) - cr[c];
+        s = fma(df, df, s);
+    }
+    terms[(size_t)b * n + i] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
 struct ClusterWs {
     double *c64q, *c64k, *w64, *pbar, *gram, *bterm, *nx2, *terms;
     uint16_t *whi, *wlo;
+    float* half_sq;
     int32_t *flags, *wmax_bits, *list_count, *list, *perm, *offsets, *chunk_hist;
     size_t bytes;
 };
@@ -724,6 +783,7 @@ static ClusterWs carve_cluster_ws(const svoo_shape* s, void* ws) {
     w.terms = c.take<double>(bh * (size_t)s->n);
     w.whi = c.take<uint16_t>(bh * kmax * s->d);
     w.wlo = c.take<uint16_t>(bh * kmax * s->d);
+    w.half_sq = c.take<float>(bh * ((kmax + 31) / 32 * 32));
     w.flags = c.take<int32_t>(3 * bh);      // flags | wmax_bits | list_count, cleared by one fill
     w.wmax_bits = w.flags + bh;
     w.list_count = w.flags + 2 * bh;
@@ -769,21 +829,21 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
         if (d == 128) {
             hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(128), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
                                k_own);
-            hipLaunchKernelGGL(assign_mfma_kernel<128>, agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi, w.wlo,
-                               w.wmax_bits, w.flags, labels, w.list, w.list_count, s->n, k_own);
+            hipLaunchKernelGGL((assign_mfma_kernel<128, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
+                               w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         } else {
             hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(128), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
                                k_own);
-            hipLaunchKernelGGL(assign_mfma_kernel<64>, agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi, w.wlo,
-                               w.wmax_bits, w.flags, labels, w.list, w.list_count, s->n, k_own);
+            hipLaunchKernelGGL((assign_mfma_kernel<64, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
+                               w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         }
         dim3 lgrid(s->n < 256 ? s->n : 256, bh);
         if (d == 128)
             hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
-                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, labels, s->n);
+                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
         else
             hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
-                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, labels, s->n);
+                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
     } else {
         dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels,
                                          nullptr, stream);
@@ -874,4 +934,82 @@ extern "C" int svoo_assign(const svoo_shape* shape, const void* x, const float* 
     hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n_own + 255) / 256), dim3(256), 0, stream, c_own, w.c64q, n_own);
     hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n_opp + 255) / 256), dim3(256), 0, stream, c_opp, w.c64k, n_opp);
     return assign_side(&s, w, x, w.c64q, k_own, w.c64k, k_opp, labels, false, stream);
+}
+
+// One Lloyd assignment: labels of x against centroids c64 [bh, k, d].
+static int kmeans_assign(const svoo_shape* s, const ClusterWs& w, const void* x, const double* c64, int k,
+                         int32_t* labels, hipStream_t stream) {
+    const int d = s->d, bh = s->bh, kpad = (k + 31) / 32 * 32;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((3 * bh + 255) / 256), dim3(256), 0, stream, w.flags, 0,
+                       (size_t)3 * bh);
+    hipLaunchKernelGGL(kmeans_prep_kernel, dim3(kpad, bh), dim3(128), 0, stream, c64, w.bterm, w.half_sq, k, kpad, d);
+    if (s->dtype == SVOO_BF16) {
+        dim3 sgrid(k, bh), agrid((s->n + 255) / 256, bh), lgrid(s->n < 256 ? s->n : 256, bh);
+        if (d == 128) {
+            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(128), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
+            hipLaunchKernelGGL((assign_mfma_kernel<128, true>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
+                               w.wlo, w.wmax_bits, w.flags, w.half_sq, labels, w.list, w.list_count, s->n, k);
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               c64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
+        } else {
+            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(128), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
+            hipLaunchKernelGGL((assign_mfma_kernel<64, true>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
+                               w.wlo, w.wmax_bits, w.flags, w.half_sq, labels, w.list, w.list_count, s->n, k);
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               c64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
+        }
+    } else {
+        dispatch_token_tile<MODE_ARGMAX>(s, x, c64, k, w.bterm, w.flags, nullptr, nullptr, nullptr, 1, labels, nullptr,
+                                         stream);
+    }
+    return launch_status();
+}
+
+// workspace layout of svoo_kmeans: the co-clustering layout with the centroids in the "q" slot
+static svoo_shape kmeans_ws_shape(const svoo_shape* shape, int k) {
+    svoo_shape s = *shape;
+    s.kq = k;
+    s.kk = 1;
+    return s;
+}
+
+size_t kmeans_ws_bytes(const svoo_shape* shape, int k) {
+    const svoo_shape s = kmeans_ws_shape(shape, k);
+    return carve_cluster_ws(&s, nullptr).bytes;
+}
+
+extern "C" int svoo_kmeans(const svoo_shape* shape, const void* x, int32_t k, const int32_t* init_idx,
+                           const float* init_c, int32_t iters, int32_t* labels, float* c, int32_t* counts,
+                           double* inertia, void* ws, size_t ws_bytes, void* hip_stream) {
+    int st = check_shape(shape, false);
+    if (st != SVOO_OK) return st;
+    if (!x || !labels || !c || !counts || !ws || (!init_idx && !init_c)) return SVOO_ERR_INVALID_ARG;
+    if (k < 1 || k > SVOO_MAX_K || k > shape->n || iters < 1 || iters > 1000) return SVOO_ERR_INVALID_ARG;
+    if (!aligned16(x) || (((uintptr_t)ws) & 255u) != 0 || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    const svoo_shape s = kmeans_ws_shape(shape, k);
+    const ClusterWs w = carve_cluster_ws(&s, ws);
+    if (ws_bytes < w.bytes) return SVOO_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    launch_init_centroids(&s, x, init_idx, init_c, w.c64q, k, stream);
+    for (int it = 0; it < iters; ++it) {
+        const bool last = it == iters - 1;
+        st = kmeans_assign(&s, w, x, w.c64q, k, labels, stream);
+        if (st != SVOO_OK) return st;
+        if (inertia) {
+            dim3 grid((s.n + 255) / 256, s.bh);
+            if (s.dtype == SVOO_BF16)
+                hipLaunchKernelGGL(kmeans_inertia_terms_kernel<uint16_t>, grid, dim3(256), 0, stream,
+                                   (const uint16_t*)x, w.c64q, labels, w.terms, s.n, k, s.d);
+            else
+                hipLaunchKernelGGL(kmeans_inertia_terms_kernel<float>, grid, dim3(256), 0, stream, (const float*)x,
+                                   w.c64q, labels, w.terms, s.n, k, s.d);
+            hipLaunchKernelGGL(objective_sum_kernel, dim3(s.bh), dim3(1024), 0, stream, w.terms, inertia + it, s.n,
+                               iters);
+        }
+        st = sort_labels(s.bh, s.n, k, labels, w.perm, w.offsets, nullptr, w.chunk_hist, stream);
+        if (st != SVOO_OK) return st;
+        launch_centroid_update(&s, x, w.perm, w.offsets, w.c64q, last ? c : nullptr, last ? counts : nullptr, k,
+                               stream);
+    }
+    return launch_status();
 }

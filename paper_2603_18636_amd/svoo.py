@@ -39,6 +39,7 @@ _SIGNATURES = {
     "svoo_cocluster": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _vp, _sz, _vp]),
     "svoo_assign": (ctypes.c_int, [_SP, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
+    "svoo_kmeans": (ctypes.c_int, [_SP, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_permute": (ctypes.c_int, [_SP, _vp, _i32, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _vp, _vp,
                                     _sz, _vp]),
     "svoo_gather": (ctypes.c_int, [_SP, _vp, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp]),
@@ -165,6 +166,29 @@ def cocluster(q, k, init_q_idx=None, init_k_idx=None, iters=2, kq=None, kk=None,
     _run(st, "svoo_cocluster")
     if obj is not None:
         out["objective"] = obj
+    return out
+
+
+def kmeans(x, init_idx=None, iters=2, k=None, init_c=None, want_inertia=False, ws=None):
+    """svoo_kmeans: independent Lloyd k-means of one tensor.  Returns dict(labels, c, counts[, inertia])."""
+    bh, n, d = x.shape
+    k = k or (init_idx.shape[1] if init_idx is not None else init_c.shape[1])
+    shape = make_shape(x, k, k)
+    _check(x, None, (bh, n, d), "x")
+    _check(init_idx, torch.int32, (bh, k), "init_idx")
+    _check(init_c, torch.float32, (bh, k, d), "init_c")
+    dev = x.device
+    out = {"labels": torch.empty((bh, n), dtype=torch.int32, device=dev),
+           "c": torch.empty((bh, k, d), dtype=torch.float32, device=dev),
+           "counts": torch.empty((bh, k), dtype=torch.int32, device=dev)}
+    inertia = torch.empty((bh, iters), dtype=torch.float64, device=dev) if want_inertia else None
+    ws = workspace(shape, dev) if ws is None else ws
+    st = _lib().svoo_kmeans(ctypes.byref(shape), _ptr(x), k, _ptr(init_idx), _ptr(init_c), iters,
+                            _ptr(out["labels"]), _ptr(out["c"]), _ptr(out["counts"]), _ptr(inertia), _ptr(ws),
+                            ws.numel(), _stream())
+    _run(st, "svoo_kmeans")
+    if inertia is not None:
+        out["inertia"] = inertia
     return out
 
 
@@ -343,6 +367,16 @@ class Layer:
                                 _ptr(self.counts_q), _ptr(self.counts_k), None, _ptr(self.ws), self.ws.numel(),
                                 _stream()), "svoo_cocluster")
 
+    def step_kmeans(self, q, k, init_q_idx, init_k_idx, iters):
+        """Independent partitioner (ablation "w/o On"): K-means of Q and of K, one after the other."""
+        lib, s = _lib(), self.shape
+        _run(lib.svoo_kmeans(ctypes.byref(s), _ptr(q), self.kq, _ptr(init_q_idx), None, iters, _ptr(self.labels_q),
+                             _ptr(self.cq), _ptr(self.counts_q), None, _ptr(self.ws), self.ws.numel(), _stream()),
+             "svoo_kmeans(q)")
+        _run(lib.svoo_kmeans(ctypes.byref(s), _ptr(k), self.kk, _ptr(init_k_idx), None, iters, _ptr(self.labels_k),
+                             _ptr(self.ck), _ptr(self.counts_k), None, _ptr(self.ws), self.ws.numel(), _stream()),
+             "svoo_kmeans(k)")
+
     def step_permute(self, q, k, v):
         lib, s = _lib(), self.shape
         src = (ctypes.c_void_p * 1)(q.data_ptr())
@@ -379,30 +413,52 @@ class Layer:
                                  _ptr(self.block_list), _ptr(self.bitmap), _ptr(self.ws), self.ws.numel(),
                                  _stream()), "svoo_block_mask")
 
-    def step_attn(self, scale):
+    def step_attn(self, scale, lse=None):
         lib, s = _lib(), self.shape
         _run(lib.svoo_block_sparse_attn(ctypes.byref(s), _ptr(self.q_sorted), _ptr(self.k_sorted),
                                         _ptr(self.v_sorted), _ptr(self.q_offsets), _ptr(self.k_offsets),
                                         _ptr(self.block_count), _ptr(self.block_list), scale, _ptr(self.o_sorted),
-                                        None, _ptr(self.ws), self.ws.numel(), _stream()), "svoo_block_sparse_attn")
+                                        _ptr(lse), _ptr(self.ws), self.ws.numel(), _stream()), "svoo_block_sparse_attn")
 
     def step_unpermute(self):
         lib, s = _lib(), self.shape
         _run(lib.svoo_unpermute(ctypes.byref(s), _ptr(self.o_sorted), _ptr(self.perm_q), _ptr(self.out), _stream()),
              "svoo_unpermute")
 
-    def run(self, q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None):
+    def run(self, q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None, partitioner="cocluster"):
         scale = 1.0 / math.sqrt(self.d) if scale is None else scale
-        self.step_cocluster(q, k, init_q_idx, init_k_idx, iters)
+        if partitioner == "cocluster":
+            self.step_cocluster(q, k, init_q_idx, init_k_idx, iters)
+        elif partitioner == "kmeans":
+            self.step_kmeans(q, k, init_q_idx, init_k_idx, iters)
+        else:
+            raise ValueError(partitioner)
         self.step_permute(q, k, v)
         self.step_block_mask(keep, tau, theta, scale)
         self.step_attn(scale)
         self.step_unpermute()
         return self.out
 
-    def dense(self, q, k, v, scale=None):
+    def dense(self, q, k, v, scale=None, lse=None):
         scale = 1.0 / math.sqrt(self.d) if scale is None else scale
         lib, s = _lib(), self.shape
-        _run(lib.svoo_attn(ctypes.byref(s), _ptr(q), _ptr(k), _ptr(v), scale, _ptr(self.out), None, _ptr(self.ws),
-                           self.ws.numel(), _stream()), "svoo_attn")
+        _run(lib.svoo_attn(ctypes.byref(s), _ptr(q), _ptr(k), _ptr(v), scale, _ptr(self.out), _ptr(lse),
+                           _ptr(self.ws), self.ws.numel(), _stream()), "svoo_attn")
         return self.out
+
+    def row_recall(self, q, k, v, scale=None):
+        """Diagnostic, not a step of the path: per token, the dense softmax mass that falls on the keys
+        of its kept blocks, = exp(LSE over kept keys - LSE over all keys), from the two attention
+        kernels' log-sum-exp outputs for the partition, permutation and block lists this object
+        holds.  [bh, n] float32 in token order; its mean is the attention recall of the paper's
+        clustering comparison.  Runs both attentions (overwrites ``out`` and ``o_sorted``)."""
+        scale = 1.0 / math.sqrt(self.d) if scale is None else scale
+        bh, n = self.labels_q.shape
+        lse_s = torch.empty((bh, n), dtype=torch.float32, device=self.dev)
+        lse_d = torch.empty((bh, n), dtype=torch.float32, device=self.dev)
+        self.step_attn(scale, lse=lse_s)
+        self.dense(q, k, v, scale, lse=lse_d)
+        rec_sorted = torch.exp(lse_s - torch.gather(lse_d, 1, self.perm_q.long()))
+        rec = torch.empty_like(rec_sorted)
+        rec.scatter_(1, self.perm_q.long(), rec_sorted)
+        return rec

@@ -44,6 +44,8 @@ def test_workspace_bytes_and_shape_validation(lib):
     need = svoo.workspace_bytes(good)
     assert need > 0 and need % 256 == 0
     assert need < 2 ** 31  # well under a GB-scale budget for the headline workload
+    # asymmetric cluster counts: the workspace also covers svoo_kmeans with k = the larger count
+    assert svoo.workspace_bytes(svoo.Shape(2, 5000, 128, svoo.SVOO_BF16, 8, 1024)) > 0
     for bad in (svoo.Shape(0, 100, 128, 0, 4, 4), svoo.Shape(1, 0, 128, 0, 4, 4), svoo.Shape(1, 100, 96, 0, 4, 4),
                 svoo.Shape(1, 100, 128, 7, 4, 4), svoo.Shape(1, 100, 128, 0, 0, 4), svoo.Shape(1, 100, 128, 0, 4, 2000),
                 svoo.Shape(1, 100, 128, 0, 200, 4)):
@@ -95,6 +97,11 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
     assert lib.svoo_unpermute(sp, fake, null, ctypes.c_void_p(0x2000), null) == INVALID
     assert lib.svoo_assign(sp, fake, fake, 0, fake, 4, fake, fake, ws_bytes, null) == INVALID
     assert lib.svoo_assign(sp, fake, fake, 4, fake, 4, fake, fake, 8, null) == TOO_SMALL
+    assert lib.svoo_kmeans(sp, fake, 16, null, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID  # no start
+    assert lib.svoo_kmeans(sp, fake, 0, fake, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID
+    assert lib.svoo_kmeans(sp, fake, 2000, fake, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID
+    assert lib.svoo_kmeans(sp, fake, 16, fake, null, 0, fake, fake, fake, null, fake, ws_bytes, null) == INVALID
+    assert lib.svoo_kmeans(sp, fake, 16, fake, null, 2, fake, fake, fake, null, fake, 64, null) == TOO_SMALL
 
 
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):

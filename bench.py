@@ -48,6 +48,8 @@ def parse_args():
                    help="also time one re-clustering period: 1 full step + (reuse-1) steps that keep labels, "
                         "permutations and block lists (0 = skip)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-partitioner-comparison", action="store_true",
+                   help="skip the recall comparison of co-clustering against independent k-means")
     p.add_argument("--gen-workers", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
     return p.parse_args()
 
@@ -216,6 +218,34 @@ def main():
                  if (0, 0) in cache else None}
         print(f"[bench] reuse period of {args.reuse}: {period_ms:.2f} ms/step amortised", file=sys.stderr, flush=True)
 
+    # ---- co-clustering against independent K-means at the same budget (clustering-strategy comparison of
+    # the paper, ablation "w/o On"): attention recall = dense softmax mass on kept keys, from the kernels' LSEs
+    comparison = None
+    if not args.no_partitioner_comparison:
+        x = inputs[0]
+        kp = torch.full((cfg.heads,), 0.2, dtype=torch.float32, device=dev)
+        comparison = {"keep": 0.2, "selection": "budget (tau=1, theta=0)", "layer_input": 0}
+        for name, part in (("cocluster", lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"],
+                                                                          x["init_k_idx"], cfg.iters)),
+                           ("kmeans", lambda: layer_obj.step_kmeans(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"],
+                                                                    cfg.iters))):
+            part()
+            torch.cuda.synchronize()
+            p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            p0.record()
+            part()
+            p1.record()
+            layer_obj.step_permute(x["q"], x["k"], x["v"])
+            layer_obj.step_block_mask(kp, 1.0, 0.0, scale)
+            rec = layer_obj.row_recall(x["q"], x["k"], x["v"], scale)
+            torch.cuda.synchronize()
+            pairs = torch.einsum("bq,bqk,bk->", layer_obj.counts_q.double(), layer_obj.bitmap.double(),
+                                 layer_obj.counts_k.double()).item()
+            comparison[name] = {"attention_recall": round(float(rec.double().mean().item()), 4),
+                                "kept_fraction": round(pairs / (cfg.heads * float(cfg.n) ** 2), 4),
+                                "partition_ms": round(p0.elapsed_time(p1), 3)}
+        print(f"[bench] partitioner comparison: {comparison}", file=sys.stderr, flush=True)
+
     attn_ms = step_ms[:, 3]
     attn_tflops = float(kept_flops.sum() / (attn_ms.sum() * 1e-3) / 1e12)
     value = total_kept / elapsed / 1e12
@@ -248,6 +278,8 @@ def main():
     }
     if reuse is not None:
         result["clustering_reuse"] = reuse
+    if comparison is not None:
+        result["partitioner_comparison"] = comparison
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], keeps[0], tau, theta, scale, float(kept_flops[0]))

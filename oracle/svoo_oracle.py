@@ -16,6 +16,9 @@ What follows the paper and where:
   Sec. 4.1 (definition of z_i), restricted to the kept (query block, key block) pairs.
 * ``kmeans`` -- the independent K-means partitioner of the ablation "w/o On" and of the prior work
   the paper contrasts itself with ("Difference from SVG2"): textbook Lloyd iterations per side.
+* ``minimal_prefix`` / ``attention_density`` / ``sparsity_schedule`` -- the offline profiling
+  module of Sec. 4.1: attention density (minimal fraction of entries covering a share tau of each
+  row's mass) and the Gaussian upper-quantile schedule built on it.
 * ``row_recall`` / ``attention_recall`` -- the attention-recall measure of the clustering
   comparison section, read as the dense softmax mass on kept keys.
 
@@ -32,7 +35,8 @@ permutation invariance, one Lloyd iteration against scikit-learn when the affini
 identity, cosine-distance argmin against SciPy, block selection against brute-force block sums of
 the exact attention matrix on zero-variance clusters, hand-computed selection cases; k-means
 against SciPy's and scikit-learn's Lloyd iterations from the same start; recall against the
-log-sum-exp identity, the uniform-attention closed form and explicit loops.  Whether the
+log-sum-exp identity, the uniform-attention closed form and explicit loops; density against
+uniform and geometric rows (closed forms), hand cases at the tau boundary and explicit loops.  Whether the
 paper's authors' code would produce the same labels is *parity unpinned*: Norm, the weighting of
 the block estimate, Recall and the meaning of s cannot be confirmed from the text alone.
 """
@@ -333,6 +337,53 @@ def row_recall(q, k, labels_q, labels_k, mask, scale, rows) -> np.ndarray:
 def attention_recall(q, k, v_unused, labels_q, labels_k, mask, scale, rows) -> float:
     """Mean of ``row_recall`` over the given rows (diagnostic)."""
     return float(row_recall(q, k, labels_q, labels_k, mask, scale, rows).mean())
+
+
+# --------------------------------------------------------------------------------------------
+# Offline profiling: attention density (Sec. 4.1, the offline profiling module)
+# --------------------------------------------------------------------------------------------
+def minimal_prefix(a: np.ndarray, tau: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Per row of the probability matrix a: entries sorted in descending order, the length of the
+    shortest prefix whose sum reaches tau (a prefix whose sum equals tau exactly is long enough),
+    capped at the row length.  Also returns how far the cumulative sum is from tau on either
+    side of the crossing (small = the length hangs on rounding)."""
+    a = np.asarray(a, np.float64)
+    n = a.shape[1]
+    c = np.cumsum(-np.sort(-a, axis=1), axis=1)
+    length = np.minimum((c < tau).sum(axis=1) + 1, n)
+    idx = np.arange(a.shape[0])
+    above = c[idx, length - 1] - tau
+    below = np.where(length > 1, tau - c[idx, np.maximum(length - 2, 0)], np.inf)
+    return length.astype(np.int64), np.minimum(np.abs(above), below)
+
+
+def attention_density(q, k, scale: float, tau: float, rows: Optional[np.ndarray] = None,
+                      chunk: int = 512) -> Dict[str, object]:
+    """Density of one head's attention map: for every (given) query row the minimal fraction of
+    the n post-softmax entries that covers a share tau of the row's mass, averaged over rows
+    (the equation defining d_{l,h}; the paper sets tau = 0.95).  The softmax is the dense one of
+    Sec. 4.1 over all n keys."""
+    q = np.asarray(q, np.float64)
+    k = np.asarray(k, np.float64)
+    n = k.shape[0]
+    rows = np.arange(q.shape[0]) if rows is None else np.asarray(rows)
+    lengths = np.empty(rows.shape[0], dtype=np.int64)
+    slack = np.empty(rows.shape[0])
+    for a0 in range(0, rows.shape[0], chunk):
+        r = rows[a0:a0 + chunk]
+        lengths[a0:a0 + chunk], slack[a0:a0 + chunk] = minimal_prefix(_softmax_rows(scale * (q[r] @ k.T)), tau)
+    return {"prefix_len": lengths, "slack": slack, "density": float((lengths / n).mean())}
+
+
+def sparsity_schedule(densities: np.ndarray, alpha: float = 0.95) -> float:
+    """From the densities of one (layer, head) over the calibration inputs to its sparsity:
+    Gaussian fit (mean, standard deviation of the samples), upper alpha-quantile as the
+    conservative density, s = 1 - that (the two equations after the density definition).  The
+    standard deviation is the maximum-likelihood one (divide by m); the text does not say which."""
+    from scipy.stats import norm as gaussian
+    d = np.asarray(densities, np.float64)
+    d_hat = d.mean() + gaussian.ppf(alpha) * d.std()
+    return float(1.0 - d_hat)
 
 
 def layer(q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None, norm="l2",

@@ -450,3 +450,63 @@ def test_recall_of_uniform_attention_is_the_kept_key_fraction():
     rr = so.row_recall(q0, h["k"], lq, lk, mask, 0.25, np.arange(n))
     np.testing.assert_allclose(rr, (mask[lq] * nk[None, :]).sum(1) / n, rtol=1e-13)
     assert abs(rr.mean() - so.kept_fraction(mask, nq, nk)) < 1e-13
+
+
+# ---------------------------------------------------------------------------- attention density (offline profiling)
+def test_minimal_prefix_hand_cases():
+    """Density definition of Sec. 4.1: shortest descending-sorted prefix reaching tau; reaching it
+    exactly is enough; order of the input does not matter."""
+    a = np.array([[0.25, 0.5, 0.125, 0.125], [0.125, 0.125, 0.5, 0.25]])
+    for tau, want in ((0.5, 1), (0.51, 2), (0.75, 2), (0.76, 3), (0.875, 3), (0.9, 4), (1.0, 4), (1e-9, 1)):
+        got, _ = so.minimal_prefix(a, tau)
+        assert got.tolist() == [want, want], (tau, got)
+    got, slack = so.minimal_prefix(np.array([[0.7, 0.2, 0.1]]), 0.8)
+    assert got[0] == 2 and abs(slack[0] - 0.1) < 1e-15
+
+
+def test_density_of_uniform_and_geometric_rows():
+    rng = np.random.default_rng(0)
+    n, d = 128, 8
+    k = rng.standard_normal((n, d))
+    # zero queries: uniform attention, the prefix is ceil(tau n) entries
+    r = so.attention_density(np.zeros((5, d)), k, 0.3, 0.95)
+    assert (r["prefix_len"] == math.ceil(0.95 * n)).all() and abs(r["density"] - math.ceil(0.95 * n) / n) < 1e-15
+    # one-dimensional keys -j ln2 / scale against q = 1: p_j proportional to 2^-j, prefix sum 1 - 2^-m
+    kk = (-np.arange(n) * math.log(2.0) / 0.3)[:, None]
+    for tau, want in ((0.9, 4), (0.5, 1), (0.75, 2), (0.76, 3), (0.999, 10)):
+        r = so.attention_density(np.ones((3, 1)), kk, 0.3, tau)
+        assert (r["prefix_len"] == want).all(), (tau, r["prefix_len"])
+        assert want == max(1, math.ceil(round(math.log2(1.0 / (1.0 - tau)), 9)))
+
+
+def test_density_matches_explicit_loops_and_row_subset():
+    h = tiny_head(7)
+    q, k = h["q"].astype(np.float64), h["k"].astype(np.float64)
+    n = q.shape[0]
+    rows = np.array([0, 3, 50, n - 1])
+    r = so.attention_density(q, k, 0.25, 0.95, rows=rows)
+    for pos, i in enumerate(rows):
+        e = [math.exp(0.25 * float(np.dot(q[i], k[t]))) for t in range(n)]
+        z = sum(e)
+        acc, cnt = 0.0, 0
+        for val in sorted(e, reverse=True):
+            acc += val / z
+            cnt += 1
+            if acc >= 0.95:
+                break
+        assert r["prefix_len"][pos] == cnt
+    full = so.attention_density(q, k, 0.25, 0.95)
+    assert (full["prefix_len"][rows] == r["prefix_len"]).all()
+    assert abs(full["density"] - full["prefix_len"].mean() / n) < 1e-15
+    lens = [so.attention_density(q, k, 0.25, t, rows=rows)["prefix_len"] for t in (0.5, 0.8, 0.95, 1.0)]
+    assert all((a <= b).all() for a, b in zip(lens, lens[1:])) and (lens[-1] <= n).all()
+
+
+def test_sparsity_schedule_is_the_gaussian_upper_quantile():
+    from scipy.stats import norm as gaussian
+    d = np.array([0.30, 0.34, 0.32, 0.36, 0.28])
+    s = so.sparsity_schedule(d, 0.95)
+    mu, sigma = 0.32, math.sqrt(((d - 0.32) ** 2).mean())
+    assert abs(s - (1.0 - (mu + 1.6448536269514722 * sigma))) < 1e-12
+    assert abs(gaussian.cdf((1.0 - s - mu) / sigma) - 0.95) < 1e-12
+    assert so.sparsity_schedule(np.full(4, 0.4), 0.95) == pytest.approx(0.6)

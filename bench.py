@@ -48,6 +48,8 @@ def parse_args():
                    help="also time one re-clustering period: 1 full step + (reuse-1) steps that keep labels, "
                         "permutations and block lists (0 = skip)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-density", action="store_true", help="skip the offline attention-density measurement")
+    p.add_argument("--density-rows", type=int, default=2048, help="sampled query rows per head for the density")
     p.add_argument("--no-partitioner-comparison", action="store_true",
                    help="skip the recall comparison of co-clustering against independent k-means")
     p.add_argument("--gen-workers", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
@@ -246,6 +248,29 @@ def main():
                                 "partition_ms": round(p0.elapsed_time(p1), 3)}
         print(f"[bench] partitioner comparison: {comparison}", file=sys.stderr, flush=True)
 
+    # ---- offline profiling (Sec. 4.1): attention density of layer input 0 on a row sample, tau = 0.95
+    density = None
+    if not args.no_density:
+        x = inputs[0]
+        n_rows = min(cfg.n, args.density_rows)
+        rows = torch.from_numpy(np.sort(np.random.default_rng(18636).choice(cfg.n, n_rows, replace=False))
+                                .astype(np.int32)).to(dev)
+        svoo.attention_density(x["q"], x["k"], 0.95, scale, rows=rows)
+        torch.cuda.synchronize()
+        q0, q1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        q0.record()
+        _, dens, passes = svoo.attention_density(x["q"], x["k"], 0.95, scale, rows=rows, want_passes=True)
+        q1.record()
+        torch.cuda.synchronize()
+        d_ms = q0.elapsed_time(q1)
+        n_pass = int(passes.max().item())
+        density = {"tau": 0.95, "rows_per_head": n_rows, "density_mean": round(float(dens.mean().item()), 5),
+                   "density_min": round(float(dens.min().item()), 5), "density_max": round(float(dens.max().item()), 5),
+                   "ms": round(d_ms, 3), "passes_max": n_pass,
+                   "score_tflops_upper": round(float(passes.double().sum().item()) * 2.0 * n_rows * cfg.n * cfg.d
+                                               / (d_ms * 1e-3) / 1e12, 1)}
+        print(f"[bench] offline density: {density}", file=sys.stderr, flush=True)
+
     attn_ms = step_ms[:, 3]
     attn_tflops = float(kept_flops.sum() / (attn_ms.sum() * 1e-3) / 1e12)
     value = total_kept / elapsed / 1e12
@@ -280,6 +305,8 @@ def main():
         result["clustering_reuse"] = reuse
     if comparison is not None:
         result["partitioner_comparison"] = comparison
+    if density is not None:
+        result["offline_density"] = density
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], keeps[0], tau, theta, scale, float(kept_flops[0]))

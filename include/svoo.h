@@ -13,7 +13,9 @@
  *   svoo_unpermute          sorted O, perm -> O in token order
  *
  * plus svoo_attn, the dense softmax(Q K^T / sqrt(d)) V used for warm-up layers/steps
- * (Sec. 5.1 "Implementations") and as the speed-up denominator.
+ * (Sec. 5.1 "Implementations") and as the speed-up denominator; svoo_kmeans, the independent
+ * partitioner of the ablation; and svoo_attention_density, the measurement of the offline
+ * profiling module that produces the per-layer budgets the online stage consumes.
  *
  * Conventions that hold for every entry point
  * -------------------------------------------
@@ -197,6 +199,26 @@ int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sorted, const 
 /* Dense attention out = softmax(scale * Q K^T) V in token order; kq, kk of the shape are ignored. */
 int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale,
               void* out, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Offline profiling: attention density (Sec. 4.1, offline profiling module, the equation defining
+ * d_{l,h}).  For slice b and query row i (all rows, or the n_rows rows listed in `rows`, one list
+ * shared by all slices, indices in [0, n)):
+ *   p_t  = softmax_t(scale * <q_i, k_t>) over all n keys of the slice,
+ *   prefix_len[b, i] = size of the shortest descending-sorted prefix of p whose sum reaches tau
+ *                      (reaching it exactly is enough; equal entries are taken as needed),
+ *   density[b] = mean_i prefix_len[b, i] / n.
+ * q, k [bh, n, d]; rows (nullable, then n_rows must equal n) [n_rows] int32; tau in (0, 1] (the
+ * paper uses 0.95); prefix_len [bh, n_rows] int32; density [bh] float64; passes (nullable) [bh]
+ * int32 = number of passes over the keys the slowest row group of the slice needed (what the
+ * call cost: passes x n_rows x n x d multiply-adds).  shape->kq / kk are ignored.  No workspace.  Logits in float32 (bf16 inputs: matrix cores, float32 accumulation),
+ * masses added in float32 within 64 keys and in float64 across them; no sort: the cut is found by
+ * bisection on the logit value, one pass over the keys per step (about 15-25 passes), so a call
+ * costs that many score-matrix computations for the listed rows.
+ */
+int svoo_attention_density(const svoo_shape* shape, const void* q, const void* k, const int32_t* rows,
+                           int32_t n_rows, float tau, float scale, int32_t* prefix_len, double* density,
+                           int32_t* passes, void* hip_stream);
 
 #ifdef __cplusplus
 }

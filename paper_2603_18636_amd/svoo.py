@@ -47,6 +47,7 @@ _SIGNATURES = {
     "svoo_block_mask": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_block_sparse_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
     "svoo_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "svoo_attention_density": (ctypes.c_int, [_SP, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -326,6 +327,24 @@ def attn(q, k, v, scale: float, want_lse=False, out=None, ws=None):
                           ws.numel(), _stream())
     _run(st, "svoo_attn")
     return (out, lse) if want_lse else out
+
+
+def attention_density(q, k, tau=0.95, scale=None, rows=None, want_passes=False):
+    """svoo_attention_density.  Returns (prefix_len [bh, n_rows] int32, density [bh] float64[, passes [bh]])."""
+    bh, n, d = q.shape
+    _check(q, None, (bh, n, d), "q")
+    _check(k, q.dtype, (bh, n, d), "k")
+    n_rows = n if rows is None else rows.shape[0]
+    _check(rows, torch.int32, (n_rows,), "rows")
+    scale = float(np.float32(1.0 / math.sqrt(d))) if scale is None else scale
+    shape = make_shape(q, 1, 1)
+    prefix_len = torch.empty((bh, n_rows), dtype=torch.int32, device=q.device)
+    density = torch.empty((bh,), dtype=torch.float64, device=q.device)
+    passes = torch.empty((bh,), dtype=torch.int32, device=q.device) if want_passes else None
+    st = _lib().svoo_attention_density(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(rows), n_rows, tau, scale,
+                                       _ptr(prefix_len), _ptr(density), _ptr(passes), _stream())
+    _run(st, "svoo_attention_density")
+    return (prefix_len, density, passes) if want_passes else (prefix_len, density)
 
 
 class Layer:

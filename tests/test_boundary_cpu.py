@@ -97,6 +97,13 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
     assert lib.svoo_unpermute(sp, fake, null, ctypes.c_void_p(0x2000), null) == INVALID
     assert lib.svoo_assign(sp, fake, fake, 0, fake, 4, fake, fake, ws_bytes, null) == INVALID
     assert lib.svoo_assign(sp, fake, fake, 4, fake, 4, fake, fake, 8, null) == TOO_SMALL
+    dens = lib.svoo_attention_density
+    assert dens(sp, fake, fake, null, 100, 0.95, 0.125, fake, fake, null, null) == INVALID    # no row list, n_rows != n
+    assert dens(sp, fake, fake, fake, 2000, 0.95, 0.125, fake, fake, null, null) == INVALID   # more rows than tokens
+    assert dens(sp, fake, fake, fake, 10, 0.0, 0.125, fake, fake, null, null) == INVALID      # tau outside (0, 1]
+    assert dens(sp, fake, fake, fake, 10, 1.5, 0.125, fake, fake, null, null) == INVALID
+    assert dens(sp, fake, null, fake, 10, 0.95, 0.125, fake, fake, null, null) == INVALID
+    assert dens(sp, fake, fake, fake, 10, 0.95, -1.0, fake, fake, null, null) == INVALID
     assert lib.svoo_kmeans(sp, fake, 16, null, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID  # no start
     assert lib.svoo_kmeans(sp, fake, 0, fake, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID
     assert lib.svoo_kmeans(sp, fake, 2000, fake, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID

@@ -266,7 +266,11 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         seg_end = seg_cum[1];
         seg_delta = seg_start[0] - seg_cum[0];
     }
-    auto issue_tile = [&](int t, int buf) {
+    // The key rows of a tile are looked up (segment walk through LDS tables, then a lane exchange)
+    // one tile ahead of their use, while matrix instructions of the current tile are in flight, so
+    // that issuing the loads right after the barrier costs address arithmetic only.
+    int next_rows[LPW];
+    auto prepare_tile = [&](int t) {          // call with t = 0, 1, 2, ... in order
         int p = t * KT + RW * wave + (lane % RW);
         p = p < total ? p : total - 1;        // rows past the end re-read the last key (masked later)
         while (p >= seg_end) {                // terminates: p < total = seg_cum[n_seg]
@@ -276,16 +280,18 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         }
         const int myrow = p + seg_delta;
 #pragma unroll
+        for (int i = 0; i < LPW; ++i) next_rows[i] = __shfl(myrow, i * RPL + lane / CPR);
+    };
+    auto issue_prepared = [&](int buf) {
+#pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int rl = i * RPL + lane / CPR;          // row within this wave's RW
-            const int row = __shfl(myrow, rl);
-            const int rho = RW * wave + rl;                // tile row
+            const int rho = RW * wave + i * RPL + lane / CPR;     // tile row
             const int kchunk = (lane % CPR) ^ (rho % CPR);
             const int vchunk = (lane % CPR) ^ vswz(rho);
-            const uint32_t goff = (uint32_t)row * ROWB;
+            const uint32_t goff = (uint32_t)next_rows[i] * ROWB;
             const int loff = buf * TILE + (RW * wave + i * RPL) * ROWB;
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kg + goff + kchunk * 16), (lds_ptr_t)(k_lds + loff), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(vg + goff + vchunk * 16), (lds_ptr_t)(v_lds + loff), 16, 0, 0);
+            load_global_to_lds_16(kg + goff + kchunk * 16, lds_address(k_lds) + loff);
+            load_global_to_lds_16(vg + goff + vchunk * 16, lds_address(v_lds) + loff);
         }
     };
 
@@ -510,9 +516,17 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2 * DB, 0);
     };
 
+    // Have the Q fragments arrive here: otherwise the compiler's wait for them sits inside the tile
+    // loop as "wait for every outstanding load" and is paid again on every tile, against the prefetch.
+#pragma unroll
+    for (int c = 0; c < DC; ++c) asm volatile("" ::"v"(qf[c]));
     // Prefetch distance NBUF-1 tiles.  Loads complete in order, so "all but the newest tiles'
     // loads" is a constant outstanding-load count while tiles are still being issued.
-    for (int t = 0; t < NBUF - 1 && t < n_tiles; ++t) issue_tile(t, t);
+    for (int t = 0; t < NBUF - 1 && t < n_tiles; ++t) {
+        prepare_tile(t);
+        issue_prepared(t);
+    }
+    if (NBUF - 1 < n_tiles) prepare_tile(NBUF - 1);
     auto run_tiles = [&](auto modec) {
         auto step = [&](auto bufc, int kt) {
             constexpr int BUF = decltype(bufc)::value;
@@ -525,8 +539,9 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             else
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();    // tile kt has landed for every wave; everyone is done with tile kt-1's buffer
-            if (kt + NBUF - 1 < n_tiles) issue_tile(kt + NBUF - 1, (BUF + NBUF - 1) % NBUF);
+            if (kt + NBUF - 1 < n_tiles) issue_prepared((BUF + NBUF - 1) % NBUF);
             if (wave_active) tile_body(bufc, modec, kt);
+            if (kt + NBUF < n_tiles) prepare_tile(kt + NBUF);
         };
         for (int kt = 0; kt < n_tiles; kt += NBUF) {
             step(std::integral_constant<int, 0>{}, kt);

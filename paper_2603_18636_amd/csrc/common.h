@@ -27,6 +27,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
 
+// Direct global -> LDS load, 16 bytes per lane: lane l of the wave lands at LDS byte address
+// lds_addr + 16 l (lds_addr wave-uniform).  Issued through inline assembly on purpose: the compiler
+// then does not track an asynchronous LDS write and puts no "wait for every outstanding load" in
+// front of later LDS reads of OTHER buffers, which would undo the prefetch.  Ordering against the
+// reads of the buffer being filled is the caller's job (s_waitcnt vmcnt(..) followed by a barrier).
+__device__ __forceinline__ void load_global_to_lds_16(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_addr))
+                 : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+
 // ---------------------------------------------------------------------------------------------
 // host-side helpers
 // ---------------------------------------------------------------------------------------------

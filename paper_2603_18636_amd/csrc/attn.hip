@@ -204,7 +204,9 @@ __device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_
 #define SVOO_SPARSE_NBUF 2
 #endif
 #define DENSE_NW 8
+#ifndef DENSE_NBUF
 #define DENSE_NBUF 3
+#endif
 #define RESCALE_LOG2 8.0f   // the running max is only raised when it is exceeded by 2^8
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;

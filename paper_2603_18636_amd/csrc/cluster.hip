@@ -494,10 +494,8 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
             const int chunk = (lane % CPR) ^ (rl % CPR);
             const uint32_t goff = (uint32_t)row * ROWB + chunk * 16;
             const int loff = buf * 2 * HALF + (wave * LPW + i) * RPL * ROWB;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(whb + goff),
-                                             (__attribute__((address_space(3))) void*)(wl + loff), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(wlb + goff),
-                                             (__attribute__((address_space(3))) void*)(wl + loff + HALF), 16, 0, 0);
+            load_global_to_lds_16(whb + goff, lds_address(wl) + loff);
+            load_global_to_lds_16(wlb + goff, lds_address(wl) + loff + HALF);
         }
     };
     issue_block(0, 0);
@@ -530,6 +528,11 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     int koff[DC];
 #pragma unroll
     for (int c = 0; c < DC; ++c) koff[c] = j * ROWB + (((2 * c + h) ^ (j % CPR)) * 16);
+    // the compiler's wait for the token loads must not end up inside the block loop
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int c = 0; c < DC; ++c) asm volatile("" ::"v"(xf[tb][c]));
 
     float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
     int bidx[2] = {0, 0};

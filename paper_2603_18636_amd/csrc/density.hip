@@ -139,9 +139,8 @@ density_bf16_kernel(DensityArgs a) {
             int row = kt * DEN_KT + rl;
             row = row < n ? row : n - 1;                            // rows past the end are masked later
             const int chunk = (lane % CPR) ^ (rl % CPR);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(kg + (size_t)row * ROWB + chunk * 16),
-                (__attribute__((address_space(3))) void*)(k_lds + buf * TILE + (wave * LPW + i) * RPL * ROWB), 16, 0, 0);
+            load_global_to_lds_16(kg + (size_t)row * ROWB + chunk * 16,
+                                  lds_address(k_lds) + buf * TILE + (wave * LPW + i) * RPL * ROWB);
         }
     };
     issue(0, 0);
@@ -156,6 +155,9 @@ density_bf16_kernel(DensityArgs a) {
     int koff[DC];
 #pragma unroll
     for (int c = 0; c < DC; ++c) koff[c] = j * ROWB + (((2 * c + h) ^ (j % CPR)) * 16);
+    // the compiler's wait for the Q loads must not end up inside the tile loop
+#pragma unroll
+    for (int c = 0; c < DC; ++c) asm volatile("" ::"v"(qf[c]));
 
     const float c2 = a.scale * LOG2E_F;
     RowState st;

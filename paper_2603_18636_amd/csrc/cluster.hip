@@ -304,14 +304,15 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
 // fixed butterfly order (xor 32, 16, ..., 1).  Same decision rule as token_tile_kernel<MODE_ARGMAX>.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(1024)
 assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int k_own,
                    const double* __restrict__ bterm, const int32_t* __restrict__ flags,
                    const double* __restrict__ nx2, const int32_t* __restrict__ list,
                    const int32_t* __restrict__ list_count, int32_t force_general, int32_t* __restrict__ labels,
                    int n) {
-    __shared__ double best_v[4];
-    __shared__ int32_t best_j[4];
+    constexpr int NWAVE = 16;
+    __shared__ double best_v[NWAVE];
+    __shared__ int32_t best_j[NWAVE];
     const int b = blockIdx.y, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     const int count = list_count[b];
     const bool general = force_general || flags[b] != 0;
@@ -328,12 +329,13 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int
         }
         double best = -INFINITY;
         int bj = 0;
-        // eight centroids per pass so that their row loads and butterfly sums overlap
-        for (int j0 = wave; j0 < k_own; j0 += 32) {
+        // eight centroids per wave and pass so that their row loads and butterfly sums overlap;
+        // a wave sees its centroids in ascending order, so a strict ">" keeps the lowest index
+        for (int j0 = wave; j0 < k_own; j0 += 8 * NWAVE) {
             double part[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int j = j0 + 4 * u;
+                const int j = j0 + NWAVE * u;
                 part[u] = 0.0;
                 if (j < k_own && 2 * lane < D) {
                     const double2 wv = *(const double2*)(wb + (size_t)j * D + 2 * lane);
@@ -346,7 +348,7 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int
                 for (int u = 0; u < 8; ++u) part[u] += __shfl_xor(part[u], off);
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int j = j0 + 4 * u;
+                const int j = j0 + NWAVE * u;
                 if (j < k_own) {
                     const double val = general ? 2.0 * part[u] - nx * bterm[(size_t)b * k_own + j] : part[u];
                     if (val > best) {
@@ -364,7 +366,7 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int
         if (threadIdx.x == 0) {
             double bv = best_v[0];
             int jj = best_j[0];
-            for (int u = 1; u < 4; ++u)
+            for (int u = 1; u < NWAVE; ++u)
                 if (best_v[u] > bv || (best_v[u] == bv && best_j[u] < jj)) {
                     bv = best_v[u];
                     jj = best_j[u];
@@ -434,34 +436,43 @@ static void dispatch_token_tile(const svoo_shape* s, const void* x, const double
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+#ifndef ASSIGN_LIST_WGS
+#define ASSIGN_LIST_WGS 256   // workgroups per slice that share the queue of undecided tokens
+#endif
 #define FAST_EPS 3.1e-5f   // 2^-16 + 256 * 2^-24, twice the analytic bound for d <= 128
 
+// 16 rows per workgroup (one wave takes four of them), one atomic per workgroup
 template <int D>
-__global__ void __launch_bounds__(128)
+__global__ void __launch_bounds__(256)
 split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo,
                int32_t* __restrict__ wmax_bits, int k_own) {
-    __shared__ double red[128];
-    const int b = blockIdx.y, j = blockIdx.x, t = threadIdx.x;
-    const size_t o = ((size_t)b * k_own + j) * D + t;
-    double v = 0.0;
-    if (t < D) {
-        v = w64[o];
-        const float hi = bf16_to_f32(f32_to_bf16((float)v));
-        const float lo = (float)(v - (double)hi);
-        whi[o] = f32_to_bf16((float)v);
-        wlo[o] = f32_to_bf16(lo);
-    }
-    red[t] = v * v;
-    __syncthreads();
-    for (int s = 64; s > 0; s >>= 1) {
-        if (t < s) red[t] += red[t + s];
-        __syncthreads();
-    }
-    if (t == 0) {
-        float nrm = (float)sqrt(red[0]);
+    __shared__ float wave_max[4];
+    const int b = blockIdx.y, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    float mx = 0.f;
+    for (int r = 0; r < 4; ++r) {
+        const int j = blockIdx.x * 16 + wave * 4 + r;
+        if (j >= k_own) break;                         // uniform per wave
+        double sq = 0.0;
+        for (int t = lane; t < D; t += 64) {
+            const size_t o = ((size_t)b * k_own + j) * D + t;
+            const double v = w64[o];
+            const uint16_t hb = f32_to_bf16((float)v);
+            whi[o] = hb;
+            wlo[o] = f32_to_bf16((float)(v - (double)bf16_to_f32(hb)));
+            sq = fma(v, v, sq);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
+        float nrm = (float)sqrt(sq);
         nrm = nrm * 1.0000002f + 1e-37f;   // round up
         if (!(nrm < 3.0e38f)) nrm = 3.0e38f;
-        atomicMax(&wmax_bits[b], __float_as_int(nrm));   // non-negative floats order like their bit patterns
+        mx = fmaxf(mx, nrm);
+    }
+    if (lane == 0) wave_max[wave] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+        atomicMax(&wmax_bits[b], __float_as_int(m));   // non-negative floats order like their bit patterns
     }
 }
 
@@ -610,50 +621,68 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // Centroid update: C[j] = mean of the member rows, float64 sums in a fixed order.
 // One workgroup per (cluster, slice); members are perm[offsets[j] .. offsets[j+1]) in ascending
-// token order.  256 threads = G row-groups of (D/2) lanes; lane l adds elements 2l, 2l+1 of the
-// rows g, g+G, g+2G, ... of its group, then the G partial sums are added in group order.
+// token order.  256 threads = G row-groups of D/8 lanes; a lane adds elements 8l .. 8l+7 (one
+// 16-byte load for bf16) of the rows g, g+G, g+2G, ... of its group, then the G partial sums are
+// added in group order.
 // ---------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void load8_as_f64(const T* p, double (&v)[8]);
+template <>
+__device__ __forceinline__ void load8_as_f64<uint16_t>(const uint16_t* p, double (&v)[8]) {
+    const uint4 u = *(const uint4*)p;
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[2 * e] = (double)__uint_as_float(w[e] << 16);
+        v[2 * e + 1] = (double)__uint_as_float(w[e] & 0xffff0000u);
+    }
+}
+template <>
+__device__ __forceinline__ void load8_as_f64<float>(const float* p, double (&v)[8]) {
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm,
                        const int32_t* __restrict__ offsets, double* __restrict__ c64, float* __restrict__ c32,
                        int32_t* __restrict__ counts, int n, int k) {
-    constexpr int LANES = D / 2;
+    constexpr int LANES = D / 8;
     constexpr int GROUPS = 256 / LANES;
     __shared__ double part[GROUPS][D];
     const int b = blockIdx.y, j = blockIdx.x;
     const int lane = threadIdx.x % LANES, grp = threadIdx.x / LANES;
     const int beg = offsets[(size_t)b * (k + 1) + j], end = offsets[(size_t)b * (k + 1) + j + 1];
     const int32_t* pm = perm + (size_t)b * n;
-    const T* xb = x + (size_t)b * n * D;
-    double s0 = 0.0, s1 = 0.0;
+    const T* xb = x + (size_t)b * n * D + 8 * lane;
+    double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int p = beg + grp;
-    for (; p + 3 * GROUPS < end; p += 4 * GROUPS) {
-        double a[4], c[4];
+    for (; p + GROUPS < end; p += 2 * GROUPS) {        // two rows in flight per lane
+        double a0[8], a1[8];
+        load8_as_f64<T>(xb + (size_t)pm[p] * D, a0);
+        load8_as_f64<T>(xb + (size_t)pm[p + GROUPS] * D, a1);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) load_pair<T>(xb + (size_t)pm[p + u * GROUPS] * D + 2 * lane, a[u], c[u]);
+        for (int e = 0; e < 8; ++e) s[e] += a0[e];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            s0 += a[u];
-            s1 += c[u];
-        }
+        for (int e = 0; e < 8; ++e) s[e] += a1[e];
     }
-    for (; p < end; p += GROUPS) {
-        double a, c;
-        load_pair<T>(xb + (size_t)pm[p] * D + 2 * lane, a, c);
-        s0 += a;
-        s1 += c;
+    if (p < end) {
+        double a0[8];
+        load8_as_f64<T>(xb + (size_t)pm[p] * D, a0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += a0[e];
     }
-    part[grp][2 * lane] = s0;
-    part[grp][2 * lane + 1] = s1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[grp][8 * lane + e] = s[e];
     __syncthreads();
     const int cnt = end - beg;
     if (threadIdx.x < D) {
         const size_t o = ((size_t)b * k + j) * D + threadIdx.x;
         if (cnt > 0) {
-            double s = part[0][threadIdx.x];
-            for (int g = 1; g < GROUPS; ++g) s += part[g][threadIdx.x];
-            c64[o] = s / (double)cnt;
+            double t = part[0][threadIdx.x];
+            for (int g = 1; g < GROUPS; ++g) t += part[g][threadIdx.x];
+            c64[o] = t / (double)cnt;
         }
         if (c32) c32[o] = (float)c64[o];
     }
@@ -828,24 +857,24 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
                                        nullptr, w.nx2, stream);
     if (s->dtype == SVOO_BF16) {
         // matrix-core pre-filter decides the clear cases; float64 decides the queued rest
-        dim3 sgrid(k_own, bh), agrid((s->n + 255) / 256, bh);
+        dim3 sgrid((k_own + 15) / 16, bh), agrid((s->n + 255) / 256, bh);
         if (d == 128) {
-            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(128), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
+            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
                                k_own);
             hipLaunchKernelGGL((assign_mfma_kernel<128, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         } else {
-            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(128), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
+            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
                                k_own);
             hipLaunchKernelGGL((assign_mfma_kernel<64, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         }
-        dim3 lgrid(s->n < 256 ? s->n : 256, bh);
+        dim3 lgrid(s->n < ASSIGN_LIST_WGS ? s->n : ASSIGN_LIST_WGS, bh);
         if (d == 128)
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
                                w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
         else
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
                                w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
     } else {
         dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels,
@@ -947,18 +976,18 @@ static int kmeans_assign(const svoo_shape* s, const ClusterWs& w, const void* x,
                        (size_t)3 * bh);
     hipLaunchKernelGGL(kmeans_prep_kernel, dim3(kpad, bh), dim3(128), 0, stream, c64, w.bterm, w.half_sq, k, kpad, d);
     if (s->dtype == SVOO_BF16) {
-        dim3 sgrid(k, bh), agrid((s->n + 255) / 256, bh), lgrid(s->n < 256 ? s->n : 256, bh);
+        dim3 sgrid((k + 15) / 16, bh), agrid((s->n + 255) / 256, bh), lgrid(s->n < ASSIGN_LIST_WGS ? s->n : ASSIGN_LIST_WGS, bh);
         if (d == 128) {
-            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(128), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
+            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
             hipLaunchKernelGGL((assign_mfma_kernel<128, true>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, w.half_sq, labels, w.list, w.list_count, s->n, k);
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
                                c64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
         } else {
-            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(128), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
+            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
             hipLaunchKernelGGL((assign_mfma_kernel<64, true>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, w.half_sq, labels, w.list, w.list_count, s->n, k);
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
                                c64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
         }
     } else {

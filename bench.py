@@ -48,6 +48,10 @@ def parse_args():
                    help="also time one re-clustering period: 1 full step + (reuse-1) steps that keep labels, "
                         "permutations and block lists (0 = skip)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--fused", action="store_true",
+                   help="time the four-call path: svoo_block_sparse_attn_tokens folds the Q gather and the "
+                        "un-permute into the attention kernel (about 0.6 %% less per layer, but the attention "
+                        "launch then also carries the row moves)")
     p.add_argument("--no-density", action="store_true", help="skip the offline attention-density measurement")
     p.add_argument("--density-rows", type=int, default=2048, help="sampled query rows per head for the density")
     p.add_argument("--no-partitioner-comparison", action="store_true",
@@ -127,13 +131,22 @@ def main():
     def one_step(i, events=None):
         x = inputs[i % n_inputs]
         kp = keep_dev[i % len(keep_dev)]
-        calls = (
-            lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
-            lambda: layer_obj.step_permute(x["q"], x["k"], x["v"]),
-            lambda: layer_obj.step_block_mask(kp, tau, theta, scale),
-            lambda: layer_obj.step_attn(scale),
-            lambda: layer_obj.step_unpermute(),
-        )
+        if not args.fused:
+            calls = (
+                lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
+                lambda: layer_obj.step_permute(x["q"], x["k"], x["v"]),
+                lambda: layer_obj.step_block_mask(kp, tau, theta, scale),
+                lambda: layer_obj.step_attn(scale),
+                lambda: layer_obj.step_unpermute(),
+            )
+        else:   # query-side row moves inside the attention kernel: no Q gather, no separate un-permute launch
+            calls = (
+                lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
+                lambda: layer_obj.step_permute_fused(x["k"], x["v"]),
+                lambda: layer_obj.step_block_mask(kp, tau, theta, scale),
+                lambda: layer_obj.step_attn_fused(x["q"], scale),
+                lambda: None,
+            )
         for c, call in enumerate(calls):
             if events is not None:
                 events[c][0].record()
@@ -289,6 +302,9 @@ def main():
                             "timed steps / wall time of the whole layer path",
         "kept_fraction_mean": round(float(np.mean(phis)), 4),
         "breakdown_ms": {name: round(float(step_ms[:, c].mean()), 3) for c, name in enumerate(STEP_NAMES)},
+        "path": "five calls (permute Q,K,V / attention / un-permute)" if not args.fused else
+                "four calls: co-clustering, permute K,V, mask, svoo_block_sparse_attn_tokens (Q gather and "
+                "un-permute inside the attention kernel; breakdown_ms.unpermute is therefore 0)",
         "sparse_attn_kept_tflops": round(attn_tflops, 2),
         "dense_attn_ms": round(dense_ms, 2) if args.dense_reps > 0 else None,
         "dense_attn_tflops": round(dense_flops / (dense_ms * 1e-3) / 1e12, 2) if args.dense_reps > 0 else None,

@@ -196,6 +196,20 @@ int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sorted, const 
                            const int32_t* block_count, const int32_t* block_list, float scale,
                            void* out_sorted, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
 
+/*
+ * The same attention with the query-side row moves folded in: q, out (and lse) are in TOKEN order
+ * and q_perm [bh, n] is the query permutation of svoo_permute (sorted row p is token q_perm[p],
+ * every value in [0, n), each once).  The kernel reads its query rows through q_perm and writes
+ * each output row straight to its token, so the caller needs neither the gather of Q (call
+ * svoo_permute on the query labels with n_tensors = 0) nor svoo_unpermute.  Same arithmetic, same
+ * results bit for bit as svoo_block_sparse_attn followed by svoo_unpermute.
+ */
+int svoo_block_sparse_attn_tokens(const svoo_shape* shape, const void* q, const int32_t* q_perm,
+                                  const void* k_sorted, const void* v_sorted, const int32_t* q_offsets,
+                                  const int32_t* k_offsets, const int32_t* block_count,
+                                  const int32_t* block_list, float scale, void* out, float* lse,
+                                  void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Dense attention out = softmax(scale * Q K^T) V in token order; kq, kk of the shape are ignored. */
 int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale,
               void* out, float* lse, void* ws, size_t ws_bytes, void* hip_stream);

@@ -77,9 +77,13 @@ struct AttnArgs {
     const int32_t* block_count;
     const int32_t* block_list;
     const int32_t* tile_prefix;
+    const int32_t* q_perm;   // nullable: q / out / lse are in token order, sorted row p is token q_perm[p]
     int n, kq, kk;
     float scale;
 };
+
+// a permutation entry outside [0, n) must not turn into an access outside the tensor
+__device__ __forceinline__ int clamp_row(int r, int n) { return r < 0 ? 0 : (r >= n ? n - 1 : r); }
 
 struct TileInfo {
     int q0, qn;    // first sorted query row of the tile, number of valid rows
@@ -311,7 +315,9 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     const bool wave_active = 32 * rwave < ti.qn;
     bf16x8 qf[DC];
     {
-        const uint4* src = (const uint4*)(qg + (size_t)(ti.q0 + (qvalid ? qrow : 0)) * D);
+        int qtok = ti.q0 + (qvalid ? qrow : 0);
+        if (a.q_perm) qtok = clamp_row(a.q_perm[(size_t)b * a.n + qtok], a.n);
+        const uint4* src = (const uint4*)(qg + (size_t)qtok * D);
 #pragma unroll
         for (int c = 0; c < DC; ++c) {
             uint4 u = qvalid ? src[2 * c + h] : make_uint4(0, 0, 0, 0);
@@ -608,20 +614,25 @@ sparse_attn_bf16_kernel(AttnArgs a) {
             }
         __builtin_amdgcn_wave_barrier();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        unsigned char* og = (unsigned char*)a.out + ((size_t)b * a.n + ti.q0 + 32 * rwave) * ROWB;
+        unsigned char* og = (unsigned char*)a.out + (size_t)b * a.n * ROWB;
+        const int row0 = ti.q0 + 32 * rwave;               // first sorted row of this wave
         const int rows_here = ti.qn - 32 * rwave;          // valid rows of this wave
+        const int32_t* pm = a.q_perm ? a.q_perm + (size_t)b * a.n : nullptr;
 #pragma unroll
         for (int i = 0; i < (32 * CPR) / 64; ++i) {
             const int e = i * 64 + lane;
             const int r = e / CPR, c = e % CPR;
             if (r < rows_here) {
                 const uint4 val = *(const uint4*)(stage + r * ROWB + ((c ^ (r % CPR)) * 16));
-                *(uint4*)(og + (size_t)r * ROWB + c * 16) = val;
+                const int dst = pm ? clamp_row(pm[row0 + r], a.n) : row0 + r;
+                *(uint4*)(og + (size_t)dst * ROWB + c * 16) = val;
             }
         }
-        if (a.lse && qvalid && h == 0)
-            a.lse[(size_t)b * a.n + ti.q0 + qrow] =
+        if (a.lse && qvalid && h == 0) {
+            const int dst = pm ? clamp_row(pm[ti.q0 + qrow], a.n) : ti.q0 + qrow;
+            a.lse[(size_t)b * a.n + dst] =
                 ltot > 0.f ? (m_used * c2 + log2f(ltot)) * 0.6931471805599453f : -INFINITY;
+        }
     }
 }
 
@@ -652,9 +663,11 @@ sparse_attn_f32_kernel(AttnArgs a) {
     const float4* kg = (const float4*)a.k + (size_t)b * a.n * (D / 4);
     const float4* vg = (const float4*)a.v + (size_t)b * a.n * (D / 4);
     float4 qv[NC], ov[NC];
+    int qtok = ti.q0 + (qvalid ? qrow : 0);     // token whose row this is: gathered / scattered through q_perm
+    if (a.q_perm) qtok = clamp_row(a.q_perm[(size_t)b * a.n + qtok], a.n);
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        qv[c] = qvalid ? qg[(size_t)(ti.q0 + qrow) * (D / 4) + 4 * c + part] : make_float4(0, 0, 0, 0);
+        qv[c] = qvalid ? qg[(size_t)qtok * (D / 4) + 4 * c + part] : make_float4(0, 0, 0, 0);
         ov[c] = make_float4(0, 0, 0, 0);
     }
     float m = -INFINITY, lsum = 0.f;
@@ -720,11 +733,11 @@ sparse_attn_f32_kernel(AttnArgs a) {
     }
     if (qvalid) {
         const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-        float4* og = (float4*)a.out + ((size_t)b * a.n + ti.q0 + qrow) * (D / 4);
+        float4* og = (float4*)a.out + ((size_t)b * a.n + qtok) * (D / 4);
 #pragma unroll
         for (int c = 0; c < NC; ++c)
             og[4 * c + part] = make_float4(ov[c].x * inv, ov[c].y * inv, ov[c].z * inv, ov[c].w * inv);
-        if (a.lse && part == 0) a.lse[(size_t)b * a.n + ti.q0 + qrow] = lsum > 0.f ? m + logf(lsum) : -INFINITY;
+        if (a.lse && part == 0) a.lse[(size_t)b * a.n + qtok] = lsum > 0.f ? m + logf(lsum) : -INFINITY;
     }
 }
 
@@ -774,10 +787,10 @@ static int launch_sparse(const svoo_shape* s, AttnArgs& a, int32_t* tile_prefix,
     return launch_status();
 }
 
-extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
-                                      const void* v_sorted, const int32_t* q_offsets, const int32_t* k_offsets,
-                                      const int32_t* block_count, const int32_t* block_list, float scale,
-                                      void* out_sorted, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
+static int sparse_attn_entry(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
+                             const void* v_sorted, const int32_t* q_perm, const int32_t* q_offsets,
+                             const int32_t* k_offsets, const int32_t* block_count, const int32_t* block_list,
+                             float scale, void* out_sorted, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
     int st = check_shape(shape, true);
     if (st != SVOO_OK) return st;
     if (!q_sorted || !k_sorted || !v_sorted || !q_offsets || !k_offsets || !block_count || !block_list ||
@@ -789,8 +802,26 @@ extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sor
     if (!(scale > 0.0f) || !(scale < 1e30f) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
     if (ws_bytes < attn_ws_bytes(shape)) return SVOO_ERR_WORKSPACE_TOO_SMALL;
     AttnArgs a = {q_sorted, k_sorted, v_sorted, out_sorted, lse, q_offsets, k_offsets, block_count, block_list,
-                  nullptr, shape->n, shape->kq, shape->kk, scale};
+                  nullptr, q_perm, shape->n, shape->kq, shape->kk, scale};
     return launch_sparse(shape, a, (int32_t*)ws, false, (hipStream_t)hip_stream);
+}
+
+extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
+                                      const void* v_sorted, const int32_t* q_offsets, const int32_t* k_offsets,
+                                      const int32_t* block_count, const int32_t* block_list, float scale,
+                                      void* out_sorted, float* lse, void* ws, size_t ws_bytes, void* hip_stream) {
+    return sparse_attn_entry(shape, q_sorted, k_sorted, v_sorted, nullptr, q_offsets, k_offsets, block_count,
+                             block_list, scale, out_sorted, lse, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int svoo_block_sparse_attn_tokens(const svoo_shape* shape, const void* q, const int32_t* q_perm,
+                                             const void* k_sorted, const void* v_sorted, const int32_t* q_offsets,
+                                             const int32_t* k_offsets, const int32_t* block_count,
+                                             const int32_t* block_list, float scale, void* out, float* lse,
+                                             void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!q_perm) return SVOO_ERR_INVALID_ARG;
+    return sparse_attn_entry(shape, q, k_sorted, v_sorted, q_perm, q_offsets, k_offsets, block_count, block_list,
+                             scale, out, lse, ws, ws_bytes, hip_stream);
 }
 
 extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale, void* out,
@@ -813,6 +844,6 @@ extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, 
     int32_t* block_list = c.take<int32_t>((size_t)s.bh);
     hipLaunchKernelGGL(dense_layout_kernel, dim3((s.bh + 255) / 256), dim3(256), 0, stream, offsets, block_count,
                        block_list, s.n, s.bh);
-    AttnArgs a = {q, k, v, out, lse, offsets, offsets, block_count, block_list, nullptr, s.n, 1, 1, scale};
+    AttnArgs a = {q, k, v, out, lse, offsets, offsets, block_count, block_list, nullptr, nullptr, s.n, 1, 1, scale};
     return launch_sparse(&s, a, tile_prefix, true, stream);
 }

@@ -46,6 +46,8 @@ _SIGNATURES = {
     "svoo_unpermute": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp]),
     "svoo_block_mask": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_block_sparse_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "svoo_block_sparse_attn_tokens": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp,
+                                                     _sz, _vp]),
     "svoo_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
     "svoo_attention_density": (ctypes.c_int, [_SP, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp]),
 }
@@ -438,6 +440,34 @@ class Layer:
                                         _ptr(self.v_sorted), _ptr(self.q_offsets), _ptr(self.k_offsets),
                                         _ptr(self.block_count), _ptr(self.block_list), scale, _ptr(self.o_sorted),
                                         _ptr(lse), _ptr(self.ws), self.ws.numel(), _stream()), "svoo_block_sparse_attn")
+
+    def step_permute_fused(self, k, v):
+        """Sort both label arrays but move only K and V: the fused attention reads Q through perm_q."""
+        lib, s = _lib(), self.shape
+        _run(lib.svoo_permute(ctypes.byref(s), _ptr(self.labels_q), self.kq, 0, None, None, _ptr(self.perm_q),
+                              _ptr(self.q_offsets), _ptr(self.ws), self.ws.numel(), _stream()), "svoo_permute(q)")
+        src = (ctypes.c_void_p * 2)(k.data_ptr(), v.data_ptr())
+        dst = (ctypes.c_void_p * 2)(self.k_sorted.data_ptr(), self.v_sorted.data_ptr())
+        _run(lib.svoo_permute(ctypes.byref(s), _ptr(self.labels_k), self.kk, 2, src, dst, _ptr(self.perm_k),
+                              _ptr(self.k_offsets), _ptr(self.ws), self.ws.numel(), _stream()), "svoo_permute(kv)")
+
+    def step_attn_fused(self, q, scale, lse=None):
+        """Attention with the Q gather and the output scatter folded in (token-order q in, ``out`` out)."""
+        lib, s = _lib(), self.shape
+        _run(lib.svoo_block_sparse_attn_tokens(ctypes.byref(s), _ptr(q), _ptr(self.perm_q), _ptr(self.k_sorted),
+                                               _ptr(self.v_sorted), _ptr(self.q_offsets), _ptr(self.k_offsets),
+                                               _ptr(self.block_count), _ptr(self.block_list), scale, _ptr(self.out),
+                                               _ptr(lse), _ptr(self.ws), self.ws.numel(), _stream()),
+             "svoo_block_sparse_attn_tokens")
+
+    def run_fused(self, q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None):
+        """The layer in four calls: co-clustering, K/V permute, mask, attention with fused query-side moves."""
+        scale = 1.0 / math.sqrt(self.d) if scale is None else scale
+        self.step_cocluster(q, k, init_q_idx, init_k_idx, iters)
+        self.step_permute_fused(k, v)
+        self.step_block_mask(keep, tau, theta, scale)
+        self.step_attn_fused(q, scale)
+        return self.out
 
     def step_unpermute(self):
         lib, s = _lib(), self.shape

@@ -85,6 +85,10 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
                                       null) == INVALID
     assert lib.svoo_block_sparse_attn(sp, fake, fake, fake, fake, fake, fake, fake, 0.125, fake, null, fake, 8,
                                       null) == TOO_SMALL
+    assert lib.svoo_block_sparse_attn_tokens(sp, fake, null, fake, fake, fake, fake, fake, fake, 0.125, fake, null, fake,
+                                             4096, null) == INVALID            # no permutation
+    assert lib.svoo_block_sparse_attn_tokens(sp, fake, fake, fake, fake, fake, fake, fake, fake, 0.125, fake, null, fake,
+                                             8, null) == TOO_SMALL
     arr = (ctypes.c_void_p * 1)(0x1000)
     arr2 = (ctypes.c_void_p * 1)(0x2000)
     assert lib.svoo_permute(sp, fake, 0, 1, arr, arr2, fake, fake, fake, ws_bytes, null) == INVALID      # 0 clusters

@@ -340,3 +340,35 @@ def test_reuse_between_reclusterings():
         mask = H.to_np(layer.bitmap)[b].astype(bool)
         ref = so.sparse_attention(drift["q"][b], drift["k"][b], drift["v"][b], lq, lk, mask, scale)
         H.assert_attn_close(out[b], ref, "bf16", f"reuse b={b}")
+
+
+# ------------------------------------------------------------------------------------------ fused query-side moves
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64)])
+def test_fused_attention_equals_permute_attention_unpermute(dtype, d):
+    """svoo_block_sparse_attn_tokens (Q read through the permutation, output rows scattered to their
+    tokens) must give exactly the bits of gather + svoo_block_sparse_attn + svoo_unpermute."""
+    h = small_cfg1_head(d=d, dtype=dtype, layer=2)
+    kq, kk, iters = 24, 20, 2
+    scale = H.scale_of(d)
+    dev = {n: H.to_dev(np.stack([h[n], h[n][::-1].copy()]), dtype) for n in "qkv"}       # two different slices
+    iq = H.to_dev(np.stack([h["init_q_idx"], h["init_q_idx"]]))
+    ik = H.to_dev(np.stack([h["init_k_idx"], h["init_k_idx"]]))
+    keep = H.to_dev(np.array([0.3, 0.6], dtype=np.float32))
+    n = h["q"].shape[0]
+    a = svoo.Layer(2, n, d, H.torch_dtype(dtype), kq, kk, H.DEV)
+    ref = a.run(dev["q"], dev["k"], dev["v"], iq, ik, iters, keep, 1.0, 0.0, scale).clone()
+    lse_sorted = torch.empty((2, n), dtype=torch.float32, device=H.DEV)
+    a.step_attn(scale, lse=lse_sorted)
+    b = svoo.Layer(2, n, d, H.torch_dtype(dtype), kq, kk, H.DEV)
+    b.out.fill_(float("nan"))
+    lse_tok = torch.empty((2, n), dtype=torch.float32, device=H.DEV)
+    b.step_cocluster(dev["q"], dev["k"], iq, ik, iters)
+    b.step_permute_fused(dev["k"], dev["v"])
+    b.step_block_mask(keep, 1.0, 0.0, scale)
+    b.step_attn_fused(dev["q"], scale, lse=lse_tok)
+    assert torch.equal(a.perm_q, b.perm_q) and torch.equal(a.q_offsets, b.q_offsets)
+    assert torch.equal(ref.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       b.out.view(torch.int16 if dtype == "bf16" else torch.int32))
+    assert torch.equal(torch.gather(lse_tok, 1, a.perm_q.long()), lse_sorted)
+    out2 = b.run_fused(dev["q"], dev["k"], dev["v"], iq, ik, iters, keep, 1.0, 0.0, scale)
+    assert torch.equal(out2.float(), ref.float())

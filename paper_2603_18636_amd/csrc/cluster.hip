@@ -390,7 +390,7 @@ static void launch_token_tile(const T* x, const double* bmat, int rows_b, const 
     // more than 64 KB of dynamic LDS has to be opted into per kernel (per device, so not cached here)
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)token_tile_lds<D>()) != hipSuccess)
-        return;
+        return;   // the failure stays recorded as HIP's last error: the caller's launch_status() reports it
     dim3 grid((n + 63) / 64, bh);
     hipLaunchKernelGGL(kern, grid, dim3(256), token_tile_lds<D>(), stream, x, bmat, rows_b, bterm, flags, nx2, list,
                        list_count, force_general, labels, quad_out, n);

@@ -338,7 +338,7 @@ def attention_density(q, k, tau=0.95, scale=None, rows=None, want_passes=False):
     _check(k, q.dtype, (bh, n, d), "k")
     n_rows = n if rows is None else rows.shape[0]
     _check(rows, torch.int32, (n_rows,), "rows")
-    scale = float(np.float32(1.0 / math.sqrt(d))) if scale is None else scale
+    scale = ctypes.c_float(1.0 / math.sqrt(d)).value if scale is None else scale
     shape = make_shape(q, 1, 1)
     prefix_len = torch.empty((bh, n_rows), dtype=torch.int32, device=q.device)
     density = torch.empty((bh,), dtype=torch.float64, device=q.device)

@@ -63,7 +63,7 @@ def test_density_row_subset_and_order():
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_density_single_key(dtype):
     x = synth.round_to_bf16(np.random.default_rng(0).standard_normal((3, 1, 128)).astype(np.float32))
-    plen, dens = svoo.attention_density(H.to_dev(x, dtype), H.to_dev(x, dtype), 0.95, H.scale_of(128))
+    plen, dens = svoo.attention_density(H.to_dev(x, dtype), H.to_dev(x, dtype))       # default tau and scale
     assert (H.to_np(plen) == 1).all() and (H.to_np(dens) == 1.0).all()
 
 

@@ -63,7 +63,7 @@ def parse_args():
 def cpu_baseline(cfg, data, keep, tau, theta, scale, kept_flops_layer):
     """The fp64 oracle, as it stands, on a bounded sample: head 0 of the first resident layer, ONE
     co-clustering iteration (both half-steps at full N), the block mask, and block-sparse attention
-    for 2048 evenly spaced query rows.  Scaled to a whole layer (x iterations, x N/2048 rows,
+    for 8192 evenly spaced query rows (about 15 s in all).  Scaled to a whole layer (x iterations, x N/8192 rows,
     x heads) and expressed in the metric's unit."""
     from oracle import svoo_oracle as so
     try:
@@ -80,7 +80,7 @@ def cpu_baseline(cfg, data, keep, tau, theta, scale, kept_flops_layer):
     mask = so.block_mask(cc["cq"].astype(np.float32).astype(np.float64), cc["ck"].astype(np.float32).astype(np.float64),
                          cc["counts_q"], cc["counts_k"], keep, tau, theta, scale)
     t_mask = time.perf_counter() - t0
-    rows = np.linspace(0, n - 1, 2048).astype(np.int64)
+    rows = np.linspace(0, n - 1, min(n, 8192)).astype(np.int64)
     t0 = time.perf_counter()
     so.sparse_attention(q, k, v, cc["labels_q"], cc["labels_k"], mask, scale, rows=rows)
     t_attn = time.perf_counter() - t0
@@ -89,7 +89,7 @@ def cpu_baseline(cfg, data, keep, tau, theta, scale, kept_flops_layer):
     return {
         "value": kept_flops_layer / layer_s / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
         "sample": (f"head 0 of layer 0: 1 of {cfg.iters} co-clustering iterations at full N ({t_iter:.1f} s), "
-                   f"block mask ({t_mask:.2f} s), sparse attention for 2048 of {n} query rows ({t_attn:.1f} s); "
+                   f"block mask ({t_mask:.2f} s), sparse attention for {rows.size} of {n} query rows ({t_attn:.1f} s); "
                    f"extrapolated to {cfg.iters} iterations, all rows, {cfg.heads} heads = {layer_s:.0f} s/layer"),
         "measured_s": t_iter + t_mask + t_attn, "extrapolated_layer_s": layer_s,
     }

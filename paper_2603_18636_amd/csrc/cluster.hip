@@ -299,63 +299,57 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
 
 // ---------------------------------------------------------------------------------------------
 // Float64 decision for the queued tokens of the matrix-core pre-filter: one workgroup per token
-// (strided over the queue), wave w scores centroids w, w+4, ...; a lane holds two elements of x,
-// reads the matching two of W_j (a coalesced 1 KB row) and the wave adds the 64 partial sums in a
-// fixed butterfly order (xor 32, 16, ..., 1).  Same decision rule as token_tile_kernel<MODE_ARGMAX>.
+// (strided over the queue), one thread per centroid (j = tid, tid + 256, ...).  The token sits in
+// LDS; thread j walks column j of the TRANSPOSED score matrix W^T [d, k_own], so that the 256
+// threads read consecutive doubles, and adds the d products in index order -- the same fixed
+// order, hence the same bits, as token_tile_kernel<MODE_ARGMAX>.  No cross-lane sums; one
+// (value, index) reduction per token at the end.
 // ---------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ void __launch_bounds__(1024)
-assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int k_own,
+__global__ void __launch_bounds__(256)
+assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wt, int k_own,
                    const double* __restrict__ bterm, const int32_t* __restrict__ flags,
                    const double* __restrict__ nx2, const int32_t* __restrict__ list,
                    const int32_t* __restrict__ list_count, int32_t force_general, int32_t* __restrict__ labels,
                    int n) {
-    constexpr int NWAVE = 16;
-    __shared__ double best_v[NWAVE];
-    __shared__ int32_t best_j[NWAVE];
-    const int b = blockIdx.y, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+    __shared__ double xs[D];
+    __shared__ double best_v[4];
+    __shared__ int32_t best_j[4];
+    const int b = blockIdx.y, tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
     const int count = list_count[b];
     const bool general = force_general || flags[b] != 0;
-    const double* wb = wmat + (size_t)b * k_own * D;
+    const double* wb = wt + (size_t)b * D * k_own;
     for (int p = blockIdx.x; p < count; p += gridDim.x) {
         const int ti = list[(size_t)b * n + p];
-        double x0 = 0.0, x1 = 0.0;
-        if (2 * lane < D) load_pair<T>(x + ((size_t)b * n + ti) * D + 2 * lane, x0, x1);
+        if (tid < D) xs[tid] = load_as_f64<T>(x + ((size_t)b * n + ti) * D + tid);
         double nx = 0.0;
         if (general) {
             const double v = nx2 ? nx2[(size_t)b * n + ti] : 1.0;   // no nx2: plain k-means scores
             const double r = sqrt(v > 0.0 ? v : 0.0);
             nx = r > NORM_FLOOR ? r : NORM_FLOOR;
         }
+        __syncthreads();
         double best = -INFINITY;
-        int bj = 0;
-        // eight centroids per wave and pass so that their row loads and butterfly sums overlap;
-        // a wave sees its centroids in ascending order, so a strict ">" keeps the lowest index
-        for (int j0 = wave; j0 < k_own; j0 += 8 * NWAVE) {
-            double part[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = j0 + NWAVE * u;
-                part[u] = 0.0;
-                if (j < k_own && 2 * lane < D) {
-                    const double2 wv = *(const double2*)(wb + (size_t)j * D + 2 * lane);
-                    part[u] = fma(x0, wv.x, x1 * wv.y);
-                }
+        int bj = 0x7fffffff;
+        for (int j = tid; j < k_own; j += 256) {         // ascending j per thread: ">" keeps the lowest index
+            const double* wc = wb + j;
+            double sum = 0.0;
+#pragma unroll 16
+            for (int c = 0; c < D; ++c) sum = fma(xs[c], wc[(size_t)c * k_own], sum);
+            const double val = general ? 2.0 * sum - nx * bterm[(size_t)b * k_own + j] : sum;
+            if (val > best || bj == 0x7fffffff) {
+                best = val;
+                bj = j;
             }
+        }
+        // (value, index) maximum, lowest index among equal values: within the wave, then across the four
 #pragma unroll
-            for (int off = 32; off > 0; off >>= 1)
-#pragma unroll
-                for (int u = 0; u < 8; ++u) part[u] += __shfl_xor(part[u], off);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int j = j0 + NWAVE * u;
-                if (j < k_own) {
-                    const double val = general ? 2.0 * part[u] - nx * bterm[(size_t)b * k_own + j] : part[u];
-                    if (val > best) {
-                        best = val;
-                        bj = j;
-                    }
-                }
+        for (int off = 32; off > 0; off >>= 1) {
+            const double ov = __shfl_xor(best, off);
+            const int oj = __shfl_xor(bj, off);
+            if (oj != 0x7fffffff && (bj == 0x7fffffff || ov > best || (ov == best && oj < bj))) {
+                best = ov;
+                bj = oj;
             }
         }
         if (lane == 0) {
@@ -363,15 +357,15 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wmat, int
             best_j[wave] = bj;
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
+        if (tid == 0) {
             double bv = best_v[0];
             int jj = best_j[0];
-            for (int u = 1; u < NWAVE; ++u)
-                if (best_v[u] > bv || (best_v[u] == bv && best_j[u] < jj)) {
+            for (int u = 1; u < 4; ++u)
+                if (best_j[u] != 0x7fffffff && (jj == 0x7fffffff || best_v[u] > bv || (best_v[u] == bv && best_j[u] < jj))) {
                     bv = best_v[u];
                     jj = best_j[u];
                 }
-            labels[(size_t)b * n + ti] = jj;
+            labels[(size_t)b * n + ti] = jj == 0x7fffffff ? 0 : jj;
         }
         __syncthreads();
     }
@@ -441,11 +435,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 #endif
 #define FAST_EPS 3.1e-5f   // 2^-16 + 256 * 2^-24, twice the analytic bound for d <= 128
 
-// 16 rows per workgroup (one wave takes four of them), one atomic per workgroup
+// 16 rows per workgroup (one wave takes four of them), one atomic per workgroup; also writes W^T in float64
 template <int D>
 __global__ void __launch_bounds__(256)
 split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo,
-               int32_t* __restrict__ wmax_bits, int k_own) {
+               double* __restrict__ wt, int32_t* __restrict__ wmax_bits, int k_own) {
     __shared__ float wave_max[4];
     const int b = blockIdx.y, wave = threadIdx.x / 64, lane = threadIdx.x % 64;
     float mx = 0.f;
@@ -459,6 +453,7 @@ split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint1
             const uint16_t hb = f32_to_bf16((float)v);
             whi[o] = hb;
             wlo[o] = f32_to_bf16((float)(v - (double)bf16_to_f32(hb)));
+            wt[((size_t)b * D + t) * k_own + j] = v;       // W^T [d, k_own] for the float64 queue kernel
             sq = fma(v, v, sq);
         }
 #pragma unroll
@@ -794,7 +789,7 @@ kmeans_inertia_terms_kernel(const T* __restrict__ x, const double* __restrict__ 
 // host side
 // ---------------------------------------------------------------------------------------------
 struct ClusterWs {
-    double *c64q, *c64k, *w64, *pbar, *gram, *bterm, *nx2, *terms;
+    double *c64q, *c64k, *w64, *wt64, *pbar, *gram, *bterm, *nx2, *terms;
     uint16_t *whi, *wlo;
     float* half_sq;
     int32_t *flags, *wmax_bits, *list_count, *list, *perm, *offsets, *chunk_hist;
@@ -808,6 +803,7 @@ static ClusterWs carve_cluster_ws(const svoo_shape* s, void* ws) {
     w.c64q = c.take<double>(bh * s->kq * s->d);
     w.c64k = c.take<double>(bh * s->kk * s->d);
     w.w64 = c.take<double>(bh * kmax * s->d);
+    w.wt64 = c.take<double>(bh * kmax * s->d);
     w.pbar = c.take<double>(bh * (size_t)s->kq * s->kk);
     w.gram = c.take<double>(bh * (size_t)s->d * s->d);
     w.bterm = c.take<double>(bh * kmax);
@@ -859,23 +855,23 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
         // matrix-core pre-filter decides the clear cases; float64 decides the queued rest
         dim3 sgrid((k_own + 15) / 16, bh), agrid((s->n + 255) / 256, bh);
         if (d == 128) {
-            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
-                               k_own);
+            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wt64,
+                               w.wmax_bits, k_own);
             hipLaunchKernelGGL((assign_mfma_kernel<128, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         } else {
-            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wmax_bits,
-                               k_own);
+            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wt64,
+                               w.wmax_bits, k_own);
             hipLaunchKernelGGL((assign_mfma_kernel<64, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         }
         dim3 lgrid(s->n < ASSIGN_LIST_WGS ? s->n : ASSIGN_LIST_WGS, bh);
         if (d == 128)
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
-                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               w.wt64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
         else
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
-                               w.w64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               w.wt64, k_own, w.bterm, w.flags, w.nx2, w.list, w.list_count, 0, labels, s->n);
     } else {
         dispatch_token_tile<MODE_ARGMAX>(s, x, w.w64, k_own, w.bterm, w.flags, w.nx2, nullptr, nullptr, 0, labels,
                                          nullptr, stream);
@@ -978,17 +974,17 @@ static int kmeans_assign(const svoo_shape* s, const ClusterWs& w, const void* x,
     if (s->dtype == SVOO_BF16) {
         dim3 sgrid((k + 15) / 16, bh), agrid((s->n + 255) / 256, bh), lgrid(s->n < ASSIGN_LIST_WGS ? s->n : ASSIGN_LIST_WGS, bh);
         if (d == 128) {
-            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
+            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, c64, w.whi, w.wlo, w.wt64, w.wmax_bits, k);
             hipLaunchKernelGGL((assign_mfma_kernel<128, true>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, w.half_sq, labels, w.list, w.list_count, s->n, k);
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
-                               c64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 128>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               w.wt64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
         } else {
-            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, c64, w.whi, w.wlo, w.wmax_bits, k);
+            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, c64, w.whi, w.wlo, w.wt64, w.wmax_bits, k);
             hipLaunchKernelGGL((assign_mfma_kernel<64, true>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, w.half_sq, labels, w.list, w.list_count, s->n, k);
-            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(1024), 0, stream, (const uint16_t*)x,
-                               c64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
+            hipLaunchKernelGGL((assign_list_kernel<uint16_t, 64>), lgrid, dim3(256), 0, stream, (const uint16_t*)x,
+                               w.wt64, k, w.bterm, w.flags, nullptr, w.list, w.list_count, 1, labels, s->n);
         }
     } else {
         dispatch_token_tile<MODE_ARGMAX>(s, x, c64, k, w.bterm, w.flags, nullptr, nullptr, nullptr, 1, labels, nullptr,

@@ -169,7 +169,8 @@ int svoo_unpermute(const svoo_shape* shape, const void* src_sorted, const int32_
  *   b     = ceil(keep[b] * kk)                          keep = fraction of key blocks kept (budget s)
  *   kept  = first (keep[b] > theta ? min(m, b) : max(m, b)) of `order`, clamped to [1, #non-empty]
  * (the threshold-dependent rule of the selection paragraph; Recall(A_bar, tau) is read as m / kk).
- * All of it in float64.  keep [bh] float32 in [0, 1] on the device; tau in (0, 1], theta any.
+ * All of it in float64 (A_bar is written to the workspace first, bh*kq*kk doubles).  keep [bh] float32
+ * in [0, 1] on the device; tau in (0, 1], theta any.
  *
  * Outputs: block_count [bh, kq]; block_list [bh, kq, kk] kept key-block ids ascending in the first
  * block_count entries (the rest is set to -1); bitmap (nullable) [bh, kq, kk] 0/1 bytes.

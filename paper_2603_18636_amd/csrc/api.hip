@@ -4,6 +4,7 @@
 size_t cluster_ws_bytes(const svoo_shape* s);
 size_t attn_ws_bytes(const svoo_shape* s);
 size_t kmeans_ws_bytes(const svoo_shape* s, int k);
+size_t mask_ws_bytes(const svoo_shape* s);
 
 extern "C" const char* svoo_status_string(int status) {
     switch (status) {
@@ -28,5 +29,7 @@ extern "C" size_t svoo_workspace_bytes(const svoo_shape* shape) {
     if (attn_need > need) need = attn_need;
     const size_t km_need = kmeans_ws_bytes(shape, kmax);   // svoo_kmeans with k = kq or kk
     if (km_need > need) need = km_need;
+    const size_t mask_need = mask_ws_bytes(shape);
+    if (mask_need > need) need = mask_need;
     return need;
 }

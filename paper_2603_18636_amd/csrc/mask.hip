@@ -4,7 +4,7 @@
 // the cost is nothing next to the attention it prunes):
 //   a_j  = scale * <cq[r], ck[j]>            coarse block estimate A_bar = C_q C_k^T
 //   w_j  = n_j exp(a_j - max) / Z            softmax over non-empty key blocks, weighted by size
-//   rank_j = #{j' : w_j' > w_j, or equal and j' < j}     (position in the descending order)
+//   rank_j = position of j in the order by descending w, equal weights by lower index (bitonic sort in LDS)
 //   m    = shortest sorted prefix with cumulative weight >= tau, summed sequentially in that order
 //   b    = ceil(keep * K_k);  kept = (keep > theta ? min(m, b) : max(m, b)) clamped to [1, #live]
 #include "common.h"
@@ -12,14 +12,53 @@
 #define MASK_THREADS 256
 #define MASK_PER_THREAD (SVOO_MAX_K / MASK_THREADS)
 
+// A_bar[b, r, j] = <cq[b, r], ck[b, j]> in float64, the d products added in index order (32 x 32
+// output tile per workgroup, 2 x 2 per thread), so that the selection kernel reads one coalesced
+// row instead of every workgroup re-reading all key centroids.
+__global__ void __launch_bounds__(256)
+block_estimate_kernel(const float* __restrict__ cq, const float* __restrict__ ck, double* __restrict__ abar, int kq,
+                      int kk, int d) {
+    __shared__ double as[16][33];
+    __shared__ double bs[16][33];
+    const int b = blockIdx.z, m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    const float* a = cq + (size_t)b * kq * d;
+    const float* bm = ck + (size_t)b * kk * d;
+    double acc[2][2] = {{0, 0}, {0, 0}};
+    for (int k0 = 0; k0 < d; k0 += 16) {
+        for (int e = threadIdx.x; e < 512; e += 256) {
+            const int c = e % 16, r = e / 16;
+            as[c][r] = (m0 + r < kq) ? (double)a[(size_t)(m0 + r) * d + k0 + c] : 0.0;
+            bs[c][r] = (n0 + r < kk) ? (double)bm[(size_t)(n0 + r) * d + k0 + c] : 0.0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const double a0 = as[c][ty * 2], a1 = as[c][ty * 2 + 1];
+            const double b0 = bs[c][tx * 2], b1 = bs[c][tx * 2 + 1];
+            acc[0][0] = fma(a0, b0, acc[0][0]);
+            acc[0][1] = fma(a0, b1, acc[0][1]);
+            acc[1][0] = fma(a1, b0, acc[1][0]);
+            acc[1][1] = fma(a1, b1, acc[1][1]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < 2; ++j) {
+            const int m = m0 + ty * 2 + i, n = n0 + tx * 2 + j;
+            if (m < kq && n < kk) abar[((size_t)b * kq + m) * kk + n] = acc[i][j];
+        }
+}
+
 __global__ void __launch_bounds__(MASK_THREADS)
-block_mask_kernel(const float* __restrict__ cq, const float* __restrict__ ck, const int32_t* __restrict__ counts_q,
+block_mask_kernel(const double* __restrict__ abar, const int32_t* __restrict__ counts_q,
                   const int32_t* __restrict__ counts_k, const float* __restrict__ keep, double tau, double theta,
                   double scale, int32_t* __restrict__ block_count, int32_t* __restrict__ block_list,
                   uint8_t* __restrict__ bitmap, int kq, int kk, int d) {
     __shared__ double w[SVOO_MAX_K];
     __shared__ double w_sorted[SVOO_MAX_K];
-    __shared__ double qrow[128];
+    __shared__ int32_t ord[SVOO_MAX_K];
+    __shared__ int32_t rank_s[SVOO_MAX_K];
     __shared__ double red[MASK_THREADS];
     __shared__ int32_t scan[MASK_THREADS];
     __shared__ int32_t n_keep_s;
@@ -35,8 +74,6 @@ block_mask_kernel(const float* __restrict__ cq, const float* __restrict__ ck, co
         if (t == 0) block_count[(size_t)b * kq + r] = 0;
         return;
     }
-    if (t < d) qrow[t] = (double)cq[((size_t)b * kq + r) * d + t];
-    __syncthreads();
 
     // logits and their maximum over non-empty key blocks
     double a[MASK_PER_THREAD];
@@ -50,10 +87,7 @@ block_mask_kernel(const float* __restrict__ cq, const float* __restrict__ ck, co
         nk[u] = 0;
         if (j < kk) {
             nk[u] = counts_k[(size_t)b * kk + j];
-            const float* kr = ck + ((size_t)b * kk + j) * d;
-            double s = 0.0;
-            for (int c = 0; c < d; ++c) s = fma(qrow[c], (double)kr[c], s);
-            a[u] = scale * s;
+            a[u] = scale * abar[row_off + j];
             if (nk[u] > 0) {
                 mx = a[u] > mx ? a[u] : mx;
                 ++live_local;
@@ -104,24 +138,59 @@ block_mask_kernel(const float* __restrict__ cq, const float* __restrict__ ck, co
     }
     __syncthreads();
 
-    // rank in the descending order (ties: lower index first); empty blocks are not ranked
+    // position in the descending order (ties: lower index first; empty blocks after all live ones)
+    if (kk <= MASK_THREADS) {
+        // few blocks: count, per block, the blocks that come before it (one block per thread)
+        if (t < kk) {
+            const double wj = w[t];
+            int rk = 0;
+            for (int o = 0; o < kk; ++o) {
+                const double wo = w[o];
+                rk += (wo > wj || (wo == wj && o < t)) ? 1 : 0;
+            }
+            ord[rk] = t;
+        }
+        __syncthreads();
+    } else {
+        // many blocks: bitonic sort of the block ids in LDS, compared through their weights
+        int P = 1;
+        while (P < kk) P <<= 1;
+        for (int i = t; i < P; i += MASK_THREADS) ord[i] = i < kk ? i : -1;     // -1 pads up to a power of two
+        __syncthreads();
+        auto before = [&](int x, int y) {     // does x come before y in the order?
+            const double wx = x < 0 ? -2.0 : w[x], wy = y < 0 ? -2.0 : w[y];
+            return wx > wy || (wx == wy && (unsigned)x < (unsigned)y);
+        };
+        for (int k2 = 2; k2 <= P; k2 <<= 1)
+            for (int j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
+                for (int i = t; i < P; i += MASK_THREADS) {
+                    const int ixj = i ^ j2;
+                    if (ixj > i) {
+                        const int x = ord[i], y = ord[ixj];
+                        const bool forward = (i & k2) == 0;
+                        if (forward ? before(y, x) : before(x, y)) {
+                            ord[i] = y;
+                            ord[ixj] = x;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+    }
+    for (int i = t; i < kk; i += MASK_THREADS) {
+        const int j = ord[i];
+        if (j >= 0) {
+            rank_s[j] = i;
+            w_sorted[i] = w[j];
+        }
+    }
+    __syncthreads();
     int rank[MASK_PER_THREAD];
 #pragma unroll
     for (int u = 0; u < MASK_PER_THREAD; ++u) {
         const int j = t + u * MASK_THREADS;
-        rank[u] = -1;
-        if (j < kk && nk[u] > 0) {
-            const double wj = w[j];
-            int rk = 0;
-            for (int o = 0; o < kk; ++o) {
-                const double wo = w[o];
-                rk += (wo > wj || (wo == wj && o < j)) ? 1 : 0;
-            }
-            rank[u] = rk;
-            w_sorted[rk] = wj;
-        }
+        rank[u] = (j < kk && nk[u] > 0) ? rank_s[j] : -1;
     }
-    __syncthreads();
 
     if (t == 0) {
         int m = n_live;
@@ -167,19 +236,24 @@ block_mask_kernel(const float* __restrict__ cq, const float* __restrict__ ck, co
     for (int j = n_keep + t; j < kk; j += MASK_THREADS) block_list[row_off + j] = -1;
 }
 
+size_t mask_ws_bytes(const svoo_shape* s) { return align_up((size_t)s->bh * s->kq * s->kk * sizeof(double), 256); }
+
 extern "C" int svoo_block_mask(const svoo_shape* shape, const float* cq, const float* ck, const int32_t* counts_q,
                                const int32_t* counts_k, const float* keep, float tau, float theta, float scale,
                                int32_t* block_count, int32_t* block_list, uint8_t* bitmap, void* ws, size_t ws_bytes,
                                void* hip_stream) {
-    (void)ws;
-    (void)ws_bytes;
     int st = check_shape(shape, true);
     if (st != SVOO_OK) return st;
     if (!cq || !ck || !counts_q || !counts_k || !keep || !block_count || !block_list) return SVOO_ERR_INVALID_ARG;
     if (!(tau > 0.0f) || !(tau <= 1.0f) || !(scale == scale) || !(theta == theta)) return SVOO_ERR_INVALID_ARG;
-    if (shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
-    hipLaunchKernelGGL(block_mask_kernel, dim3(shape->kq, shape->bh), dim3(MASK_THREADS), 0, (hipStream_t)hip_stream,
-                       cq, ck, counts_q, counts_k, keep, (double)tau, (double)theta, (double)scale, block_count,
-                       block_list, bitmap, shape->kq, shape->kk, shape->d);
+    if (shape->bh > 65535 || !ws || (((uintptr_t)ws) & 255u) != 0) return SVOO_ERR_INVALID_ARG;
+    if (ws_bytes < mask_ws_bytes(shape)) return SVOO_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    double* abar = (double*)ws;
+    hipLaunchKernelGGL(block_estimate_kernel, dim3((shape->kk + 31) / 32, (shape->kq + 31) / 32, shape->bh), dim3(256), 0,
+                       stream, cq, ck, abar, shape->kq, shape->kk, shape->d);
+    hipLaunchKernelGGL(block_mask_kernel, dim3(shape->kq, shape->bh), dim3(MASK_THREADS), 0, stream, abar, counts_q,
+                       counts_k, keep, (double)tau, (double)theta, (double)scale, block_count, block_list, bitmap,
+                       shape->kq, shape->kk, shape->d);
     return launch_status();
 }

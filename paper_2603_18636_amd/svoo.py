@@ -286,9 +286,10 @@ def block_mask(cq, ck, counts_q, counts_k, keep, tau: float, theta: float, scale
     block_count = torch.empty((bh, kq), dtype=torch.int32, device=dev)
     block_list = torch.empty((bh, kq, kk), dtype=torch.int32, device=dev)
     bitmap = torch.empty((bh, kq, kk), dtype=torch.uint8, device=dev) if want_bitmap else None
+    ws = workspace(shape, dev) if ws is None else ws
     st = _lib().svoo_block_mask(ctypes.byref(shape), _ptr(cq), _ptr(ck), _ptr(counts_q), _ptr(counts_k), _ptr(keep),
-                                tau, theta, scale, _ptr(block_count), _ptr(block_list), _ptr(bitmap), None, 0,
-                                _stream())
+                                tau, theta, scale, _ptr(block_count), _ptr(block_list), _ptr(bitmap), _ptr(ws),
+                                ws.numel(), _stream())
     _run(st, "svoo_block_mask")
     return block_count, block_list, bitmap
 

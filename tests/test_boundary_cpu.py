@@ -81,6 +81,10 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
                                null) == INVALID                      # tau outside (0, 1]
     assert lib.svoo_block_mask(sp, fake, fake, fake, fake, null, 0.9, 0.1, 0.125, fake, fake, null, null, 0,
                                null) == INVALID
+    assert lib.svoo_block_mask(sp, fake, fake, fake, fake, fake, 0.9, 0.1, 0.125, fake, fake, null, null, 0,
+                               null) == INVALID                      # the block estimate needs the workspace
+    assert lib.svoo_block_mask(sp, fake, fake, fake, fake, fake, 0.9, 0.1, 0.125, fake, fake, null, fake, 64,
+                               null) == TOO_SMALL
     assert lib.svoo_block_sparse_attn(sp, fake, fake, fake, fake, fake, fake, null, 0.125, fake, null, fake, 4096,
                                       null) == INVALID
     assert lib.svoo_block_sparse_attn(sp, fake, fake, fake, fake, fake, fake, fake, 0.125, fake, null, fake, 8,

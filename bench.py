@@ -133,16 +133,18 @@ def main():
         kp = keep_dev[i % len(keep_dev)]
         if not args.fused:
             calls = (
-                lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
-                lambda: layer_obj.step_permute(x["q"], x["k"], x["v"]),
+                # the cluster-order layout comes out of the co-clustering (its last centroid updates sort the
+                # labels anyway), so the permute step is the row gather alone
+                lambda: layer_obj.step_cocluster_sorted(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
+                lambda: layer_obj.step_regather(x["q"], x["k"], x["v"]),
                 lambda: layer_obj.step_block_mask(kp, tau, theta, scale),
                 lambda: layer_obj.step_attn(scale),
                 lambda: layer_obj.step_unpermute(),
             )
         else:   # query-side row moves inside the attention kernel: no Q gather, no separate un-permute launch
             calls = (
-                lambda: layer_obj.step_cocluster(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
-                lambda: layer_obj.step_permute_fused(x["k"], x["v"]),
+                lambda: layer_obj.step_cocluster_sorted(x["q"], x["k"], x["init_q_idx"], x["init_k_idx"], cfg.iters),
+                lambda: layer_obj.step_regather_kv(x["k"], x["v"]),
                 lambda: layer_obj.step_block_mask(kp, tau, theta, scale),
                 lambda: layer_obj.step_attn_fused(x["q"], scale),
                 lambda: None,
@@ -302,7 +304,8 @@ def main():
                             "timed steps / wall time of the whole layer path",
         "kept_fraction_mean": round(float(np.mean(phis)), 4),
         "breakdown_ms": {name: round(float(step_ms[:, c].mean()), 3) for c, name in enumerate(STEP_NAMES)},
-        "path": "five calls (permute Q,K,V / attention / un-permute)" if not args.fused else
+        "path": "five calls (svoo_cocluster_sorted / svoo_gather of Q,K,V / mask / attention / un-permute)"
+                if not args.fused else
                 "four calls: co-clustering, permute K,V, mask, svoo_block_sparse_attn_tokens (Q gather and "
                 "un-permute inside the attention kernel; breakdown_ms.unpermute is therefore 0)",
         "sparse_attn_kept_tflops": round(attn_tflops, 2),

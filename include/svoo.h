@@ -103,6 +103,21 @@ int svoo_cocluster(const svoo_shape* shape, const void* q, const void* k,
                    void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * svoo_cocluster that also hands out the cluster-order layout of the labels it returns: perm_q [bh, n],
+ * q_offsets [bh, kq+1], perm_k [bh, n], k_offsets [bh, kk+1], exactly what svoo_permute would compute
+ * from labels_q / labels_k (the last iteration's centroid updates sort the labels anyway).  The
+ * caller then moves Q, K, V with svoo_gather and skips the two sorts of svoo_permute.  All four
+ * outputs are required.
+ */
+int svoo_cocluster_sorted(const svoo_shape* shape, const void* q, const void* k,
+                          const int32_t* init_q_idx, const int32_t* init_k_idx,
+                          const float* init_cq, const float* init_ck, int32_t iters,
+                          int32_t* labels_q, int32_t* labels_k, float* cq, float* ck,
+                          int32_t* counts_q, int32_t* counts_k, double* objective,
+                          int32_t* perm_q, int32_t* q_offsets, int32_t* perm_k, int32_t* k_offsets,
+                          void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
  * One assignment of Algorithm 1 on its own (the "Assign ... to blocks" line of Step A or B):
  * x [bh, n, d] rows against own-side centroids c_own [bh, k_own, d] through the affinity to
  * c_opp [bh, k_opp, d] (float32 both).  labels [bh, n].  k_own, k_opp <= 1024.

@@ -902,10 +902,13 @@ static void launch_init_centroids(const svoo_shape* s, const void* x, const int3
                            s->n, k, s->d);
 }
 
-extern "C" int svoo_cocluster(const svoo_shape* shape, const void* q, const void* k, const int32_t* init_q_idx,
-                              const int32_t* init_k_idx, const float* init_cq, const float* init_ck, int32_t iters,
-                              int32_t* labels_q, int32_t* labels_k, float* cq, float* ck, int32_t* counts_q,
-                              int32_t* counts_k, double* objective, void* ws, size_t ws_bytes, void* hip_stream) {
+// perm_* / *_offsets (all four or none): the cluster-order layout of the returned labels, which the
+// last iteration's centroid updates need anyway
+static int cocluster_impl(const svoo_shape* shape, const void* q, const void* k, const int32_t* init_q_idx,
+                          const int32_t* init_k_idx, const float* init_cq, const float* init_ck, int32_t iters,
+                          int32_t* labels_q, int32_t* labels_k, float* cq, float* ck, int32_t* counts_q,
+                          int32_t* counts_k, double* objective, int32_t* perm_q, int32_t* q_offsets, int32_t* perm_k,
+                          int32_t* k_offsets, void* ws, size_t ws_bytes, void* hip_stream) {
     int st = check_shape(shape, true);
     if (st != SVOO_OK) return st;
     if (!q || !k || !labels_q || !labels_k || !cq || !ck || !counts_q || !counts_k || !ws)
@@ -927,21 +930,45 @@ extern "C" int svoo_cocluster(const svoo_shape* shape, const void* q, const void
         if (st != SVOO_OK) return st;
         if (objective)
             launch_objective(shape, w, k, shape->kk, labels_k, objective + (size_t)it * 2, iters * 2, stream);
-        st = sort_labels(shape->bh, shape->n, shape->kk, labels_k, w.perm, w.offsets, nullptr, w.chunk_hist, stream);
+        int32_t* pk = last && perm_k ? perm_k : w.perm;
+        int32_t* ok = last && perm_k ? k_offsets : w.offsets;
+        st = sort_labels(shape->bh, shape->n, shape->kk, labels_k, pk, ok, nullptr, w.chunk_hist, stream);
         if (st != SVOO_OK) return st;
-        launch_centroid_update(shape, k, w.perm, w.offsets, w.c64k, last ? ck : nullptr, last ? counts_k : nullptr,
-                               shape->kk, stream);
+        launch_centroid_update(shape, k, pk, ok, w.c64k, last ? ck : nullptr, last ? counts_k : nullptr, shape->kk,
+                               stream);
         // Step B: queries against the NEW key anchors, own centroids the OLD C_q.
         st = assign_side(shape, w, q, w.c64q, shape->kq, w.c64k, shape->kk, labels_q, objective != nullptr, stream);
         if (st != SVOO_OK) return st;
         if (objective)
             launch_objective(shape, w, q, shape->kq, labels_q, objective + (size_t)it * 2 + 1, iters * 2, stream);
-        st = sort_labels(shape->bh, shape->n, shape->kq, labels_q, w.perm, w.offsets, nullptr, w.chunk_hist, stream);
+        int32_t* pq = last && perm_q ? perm_q : w.perm;
+        int32_t* oq = last && perm_q ? q_offsets : w.offsets;
+        st = sort_labels(shape->bh, shape->n, shape->kq, labels_q, pq, oq, nullptr, w.chunk_hist, stream);
         if (st != SVOO_OK) return st;
-        launch_centroid_update(shape, q, w.perm, w.offsets, w.c64q, last ? cq : nullptr, last ? counts_q : nullptr,
-                               shape->kq, stream);
+        launch_centroid_update(shape, q, pq, oq, w.c64q, last ? cq : nullptr, last ? counts_q : nullptr, shape->kq,
+                               stream);
     }
     return launch_status();
+}
+
+extern "C" int svoo_cocluster(const svoo_shape* shape, const void* q, const void* k, const int32_t* init_q_idx,
+                              const int32_t* init_k_idx, const float* init_cq, const float* init_ck, int32_t iters,
+                              int32_t* labels_q, int32_t* labels_k, float* cq, float* ck, int32_t* counts_q,
+                              int32_t* counts_k, double* objective, void* ws, size_t ws_bytes, void* hip_stream) {
+    return cocluster_impl(shape, q, k, init_q_idx, init_k_idx, init_cq, init_ck, iters, labels_q, labels_k, cq, ck,
+                          counts_q, counts_k, objective, nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, hip_stream);
+}
+
+extern "C" int svoo_cocluster_sorted(const svoo_shape* shape, const void* q, const void* k, const int32_t* init_q_idx,
+                                     const int32_t* init_k_idx, const float* init_cq, const float* init_ck,
+                                     int32_t iters, int32_t* labels_q, int32_t* labels_k, float* cq, float* ck,
+                                     int32_t* counts_q, int32_t* counts_k, double* objective, int32_t* perm_q,
+                                     int32_t* q_offsets, int32_t* perm_k, int32_t* k_offsets, void* ws,
+                                     size_t ws_bytes, void* hip_stream) {
+    if (!perm_q || !q_offsets || !perm_k || !k_offsets) return SVOO_ERR_INVALID_ARG;
+    return cocluster_impl(shape, q, k, init_q_idx, init_k_idx, init_cq, init_ck, iters, labels_q, labels_k, cq, ck,
+                          counts_q, counts_k, objective, perm_q, q_offsets, perm_k, k_offsets, ws, ws_bytes,
+                          hip_stream);
 }
 
 extern "C" int svoo_assign(const svoo_shape* shape, const void* x, const float* c_own, int32_t k_own,

@@ -38,6 +38,8 @@ _SIGNATURES = {
     "svoo_workspace_bytes": (_sz, [_SP]),
     "svoo_cocluster": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _vp, _sz, _vp]),
+    "svoo_cocluster_sorted": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
+                                             _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_assign": (ctypes.c_int, [_SP, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
     "svoo_kmeans": (ctypes.c_int, [_SP, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_permute": (ctypes.c_int, [_SP, _vp, _i32, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _vp, _vp, _vp,
@@ -389,6 +391,16 @@ class Layer:
                                 _ptr(self.counts_q), _ptr(self.counts_k), None, _ptr(self.ws), self.ws.numel(),
                                 _stream()), "svoo_cocluster")
 
+    def step_cocluster_sorted(self, q, k, init_q_idx, init_k_idx, iters):
+        """Co-clustering that leaves perm_q / q_offsets / perm_k / k_offsets behind (no sorts in the permute)."""
+        lib, s = _lib(), self.shape
+        _run(lib.svoo_cocluster_sorted(ctypes.byref(s), _ptr(q), _ptr(k), _ptr(init_q_idx), _ptr(init_k_idx), None,
+                                       None, iters, _ptr(self.labels_q), _ptr(self.labels_k), _ptr(self.cq),
+                                       _ptr(self.ck), _ptr(self.counts_q), _ptr(self.counts_k), None,
+                                       _ptr(self.perm_q), _ptr(self.q_offsets), _ptr(self.perm_k),
+                                       _ptr(self.k_offsets), _ptr(self.ws), self.ws.numel(), _stream()),
+             "svoo_cocluster_sorted")
+
     def step_kmeans(self, q, k, init_q_idx, init_k_idx, iters):
         """Independent partitioner (ablation "w/o On"): K-means of Q and of K, one after the other."""
         lib, s = _lib(), self.shape
@@ -416,6 +428,12 @@ class Layer:
         src = (ctypes.c_void_p * 1)(q.data_ptr())
         dst = (ctypes.c_void_p * 1)(self.q_sorted.data_ptr())
         _run(lib.svoo_gather(ctypes.byref(s), _ptr(self.perm_q), 1, src, dst, _stream()), "svoo_gather(q)")
+        src = (ctypes.c_void_p * 2)(k.data_ptr(), v.data_ptr())
+        dst = (ctypes.c_void_p * 2)(self.k_sorted.data_ptr(), self.v_sorted.data_ptr())
+        _run(lib.svoo_gather(ctypes.byref(s), _ptr(self.perm_k), 2, src, dst, _stream()), "svoo_gather(kv)")
+
+    def step_regather_kv(self, k, v):
+        lib, s = _lib(), self.shape
         src = (ctypes.c_void_p * 2)(k.data_ptr(), v.data_ptr())
         dst = (ctypes.c_void_p * 2)(self.k_sorted.data_ptr(), self.v_sorted.data_ptr())
         _run(lib.svoo_gather(ctypes.byref(s), _ptr(self.perm_k), 2, src, dst, _stream()), "svoo_gather(kv)")
@@ -464,8 +482,8 @@ class Layer:
     def run_fused(self, q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None):
         """The layer in four calls: co-clustering, K/V permute, mask, attention with fused query-side moves."""
         scale = 1.0 / math.sqrt(self.d) if scale is None else scale
-        self.step_cocluster(q, k, init_q_idx, init_k_idx, iters)
-        self.step_permute_fused(k, v)
+        self.step_cocluster_sorted(q, k, init_q_idx, init_k_idx, iters)
+        self.step_regather_kv(k, v)
         self.step_block_mask(keep, tau, theta, scale)
         self.step_attn_fused(q, scale)
         return self.out
@@ -477,8 +495,13 @@ class Layer:
 
     def run(self, q, k, v, init_q_idx, init_k_idx, iters, keep, tau, theta, scale=None, partitioner="cocluster"):
         scale = 1.0 / math.sqrt(self.d) if scale is None else scale
-        if partitioner == "cocluster":
-            self.step_cocluster(q, k, init_q_idx, init_k_idx, iters)
+        if partitioner == "cocluster":      # the layout comes with the clustering: gather only
+            self.step_cocluster_sorted(q, k, init_q_idx, init_k_idx, iters)
+            self.step_regather(q, k, v)
+            self.step_block_mask(keep, tau, theta, scale)
+            self.step_attn(scale)
+            self.step_unpermute()
+            return self.out
         elif partitioner == "kmeans":
             self.step_kmeans(q, k, init_q_idx, init_k_idx, iters)
         else:

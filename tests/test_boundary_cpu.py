@@ -72,6 +72,10 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
                               fake, 16, null) == TOO_SMALL
     assert lib.svoo_cocluster(sp, odd, fake, fake, fake, null, null, 2, fake, fake, fake, fake, fake, fake, null,
                               fake, ws_bytes, null) == INVALID       # misaligned q
+    assert lib.svoo_cocluster_sorted(sp, fake, fake, fake, fake, null, null, 2, fake, fake, fake, fake, fake, fake, null,
+                                     fake, fake, fake, null, fake, ws_bytes, null) == INVALID   # a layout output missing
+    assert lib.svoo_cocluster_sorted(sp, fake, fake, fake, fake, null, null, 2, fake, fake, fake, fake, fake, fake, null,
+                                     fake, fake, fake, fake, fake, 16, null) == TOO_SMALL
     bad_d = svoo.Shape(1, 1024, 80, svoo.SVOO_F32, 16, 16)
     assert lib.svoo_attn(ctypes.byref(bad_d), fake, fake, fake, 0.125, fake, null, fake, 4096, null) == UNSUPPORTED
     assert lib.svoo_attn(sp, fake, fake, null, 0.125, fake, null, fake, 4096, null) == INVALID

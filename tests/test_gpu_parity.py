@@ -372,3 +372,22 @@ def test_fused_attention_equals_permute_attention_unpermute(dtype, d):
     assert torch.equal(torch.gather(lse_tok, 1, a.perm_q.long()), lse_sorted)
     out2 = b.run_fused(dev["q"], dev["k"], dev["v"], iq, ik, iters, keep, 1.0, 0.0, scale)
     assert torch.equal(out2.float(), ref.float())
+
+
+def test_cocluster_sorted_layout_equals_permute():
+    """svoo_cocluster_sorted hands out the layout svoo_permute would compute from the same labels."""
+    h = small_cfg1_head(dtype="bf16", layer=4)
+    n, kq, kk = h["q"].shape[0], 24, 20
+    dev = {x: H.to_dev(np.stack([h[x], h[x][::-1].copy()]), "bf16") for x in "qkv"}
+    iq = H.to_dev(np.stack([h["init_q_idx"], h["init_q_idx"]]))
+    ik = H.to_dev(np.stack([h["init_k_idx"], h["init_k_idx"]]))
+    a = svoo.Layer(2, n, 128, torch.bfloat16, kq, kk, H.DEV)
+    b = svoo.Layer(2, n, 128, torch.bfloat16, kq, kk, H.DEV)
+    a.step_cocluster(dev["q"], dev["k"], iq, ik, 3)
+    a.step_permute(dev["q"], dev["k"], dev["v"])
+    b.step_cocluster_sorted(dev["q"], dev["k"], iq, ik, 3)
+    b.step_regather(dev["q"], dev["k"], dev["v"])
+    for name in ("labels_q", "labels_k", "cq", "ck", "counts_q", "counts_k", "perm_q", "perm_k", "q_offsets", "k_offsets"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+    for name in ("q_sorted", "k_sorted", "v_sorted"):
+        assert torch.equal(getattr(a, name).view(torch.int16), getattr(b, name).view(torch.int16)), name

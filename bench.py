@@ -54,6 +54,8 @@ def parse_args():
                         "launch then also carries the row moves)")
     p.add_argument("--no-density", action="store_true", help="skip the offline attention-density measurement")
     p.add_argument("--density-rows", type=int, default=2048, help="sampled query rows per head for the density")
+    p.add_argument("--no-microbench", action="store_true",
+                   help="skip the matrix-core and copy microbenchmarks the fractions are also quoted against")
     p.add_argument("--no-partitioner-comparison", action="store_true",
                    help="skip the recall comparison of co-clustering against independent k-means")
     p.add_argument("--gen-workers", type=int, default=int(os.environ.get("OMP_NUM_THREADS", "8")))
@@ -286,6 +288,34 @@ def main():
                                                / (d_ms * 1e-3) / 1e12, 1)}
         print(f"[bench] offline density: {density}", file=sys.stderr, flush=True)
 
+    # ---- what this GPU sustains on the two resources the fractions are quoted against: matrix-core
+    # instructions on register operands with nothing else running, and a plain copy of one tensor
+    measured = None
+    if not args.no_microbench:
+        sink = torch.empty((2048 * 256,), dtype=torch.float32, device=dev)
+        measured = {}
+        for name, rnd in (("mfma_bf16_random_operands_tflops", True), ("mfma_bf16_constant_operands_tflops", False)):
+            svoo.microbench_mfma_bf16(sink, 2000, rnd)
+            torch.cuda.synchronize()
+            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            m0.record()
+            fl = svoo.microbench_mfma_bf16(sink, 20000, rnd)
+            m1.record()
+            torch.cuda.synchronize()
+            measured[name] = round(fl / (m0.elapsed_time(m1) * 1e-3) / 1e12, 1)
+        src, dst = inputs[0]["v"], layer_obj.v_sorted
+        svoo.microbench_copy(src, dst)
+        torch.cuda.synchronize()
+        m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        m0.record()
+        for _ in range(5):
+            moved = svoo.microbench_copy(src, dst)
+        m1.record()
+        torch.cuda.synchronize()
+        measured["copy_GBps"] = round(5 * moved / (m0.elapsed_time(m1) * 1e-3) / 1e9, 1)
+        measured["copy_bytes"] = moved
+        print(f"[bench] measured peaks: {measured}", file=sys.stderr, flush=True)
+
     attn_ms = step_ms[:, 3]
     attn_tflops = float(kept_flops.sum() / (attn_ms.sum() * 1e-3) / 1e12)
     value = total_kept / elapsed / 1e12
@@ -326,6 +356,14 @@ def main():
         result["partitioner_comparison"] = comparison
     if density is not None:
         result["offline_density"] = density
+    if measured is not None:
+        tensor_bytes = cfg.heads * cfg.n * cfg.d * (2 if cfg.dtype == "bf16" else 4)
+        perm_ms, unperm_ms = float(step_ms[:, 1].mean()), float(step_ms[:, 4].mean())
+        measured["frac_of_measured_mfma"] = round(attn_tflops / measured["mfma_bf16_random_operands_tflops"], 4)
+        if not args.fused and unperm_ms > 0:
+            measured["row_gather_GBps"] = round(6 * tensor_bytes / (perm_ms * 1e-3) / 1e9, 1)
+            measured["unpermute_GBps"] = round(2 * tensor_bytes / (unperm_ms * 1e-3) / 1e9, 1)
+        result["measured_peaks"] = measured
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample ...", file=sys.stderr, flush=True)
         result["cpu_baseline"] = cpu_baseline(cfg, host[0], keeps[0], tau, theta, scale, float(kept_flops[0]))

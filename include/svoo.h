@@ -250,6 +250,23 @@ int svoo_attention_density(const svoo_shape* shape, const void* q, const void* k
                            int32_t n_rows, float tau, float scale, int32_t* prefix_len, double* density,
                            int32_t* passes, void* hip_stream);
 
+/*
+ * Measurement aids (not part of the method; for callers that quote a kernel's rate against what
+ * this GPU sustains rather than against the data-sheet figure).
+ *
+ * svoo_microbench_mfma_bf16: `workgroups` groups of 4 waves each run `iters` x 16 bf16 matrix-core
+ * instructions (32x32x16, float32 accumulation) on register operands -- random ones if
+ * random_operands != 0, else one constant (the sustained clock depends on the data).  sink
+ * (device) [workgroups * 256] float receives values that only keep the work alive; *flops (host,
+ * nullable) receives the launch's flop count.  The caller times the launch on its stream.
+ *
+ * svoo_microbench_copy: dst[0..bytes) = src[0..bytes) (device, 16-byte aligned, bytes a multiple
+ * of 16, no overlap) with plain 16-byte loads and stores; moves 2 x bytes.
+ */
+int svoo_microbench_mfma_bf16(int32_t workgroups, int32_t iters, int32_t random_operands, float* sink,
+                              double* flops, void* hip_stream);
+int svoo_microbench_copy(const void* src, void* dst, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

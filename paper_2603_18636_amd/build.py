@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsvoo.so")
-SOURCES = ["api.hip", "sort.hip", "cluster.hip", "mask.hip", "attn.hip", "density.hip"]
+SOURCES = ["api.hip", "sort.hip", "cluster.hip", "mask.hip", "attn.hip", "density.hip", "microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -5,15 +5,16 @@
 // segment), cut into tiles of KT keys; only the last tile of the stream is ragged.  Online softmax
 // (running max and sum per query row) makes one pass over the stream.
 //
-// bf16 kernel (CDNA4 matrix cores, v_mfma_f32_32x32x16_bf16), 8 waves x 32 query rows:
+// bf16 kernel (CDNA4 matrix cores, v_mfma_f32_32x32x16_bf16), NW waves x 32 query rows:
 //   S^T = K_tile Q^T      A operand: K rows from LDS, B operand: Q, resident in registers
 //   O^T += V_tile^T P^T   A operand: V^T, read from the row-major V tile with transposing LDS reads,
 //                          B operand: P^T taken straight from the S^T accumulators
 // Computing the transposes puts one query per lane: the softmax row reductions are in-lane plus a
 // single exchange between lane l and l+32, and the probabilities are already laid out as the next
-// MFMA's B operand.  256 rows per workgroup halve the K/V traffic out of L2 per flop compared with
-// 128 (each K/V tile is fetched once per workgroup), which is what bounds this kernel once the
-// matrix pipeline is fed.
+// MFMA's B operand.  The block-sparse launch uses 4 waves (128 rows: query blocks hold a few hundred
+// rows, so larger tiles waste more of their last tile than they save); the dense launch uses 8 waves
+// (256 rows), which halves the K/V traffic out of L2 per flop (each K/V tile is fetched once per
+// workgroup).
 //
 // f32 kernel: 4 lanes per query row, plain float32 FMAs, same schedule and key stream.
 #include <type_traits>
@@ -182,9 +183,9 @@ __device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// bf16 matrix-core kernel, head dimension D (64 or 128), BM = 128 query rows per workgroup
+// bf16 matrix-core kernel, head dimension D (64 or 128), BM = 32 NW query rows per workgroup
 //
-// LDS: K and V tiles of 64 keys, row-major [key][D], double buffered, filled by direct
+// LDS: K and V tiles of 64 keys, row-major [key][D], NBUF buffers of each, filled by direct
 // global->LDS 16-byte loads (no register staging).  A wave-load writes 1 KB = lane-consecutive
 // 16-byte slots, so the 16-byte chunk c of tile row r is fetched by the lane whose slot is
 // c ^ swizzle(r): an XOR swizzle (by row for K, by row on 32-byte granules for V) that makes both

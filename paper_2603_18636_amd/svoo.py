@@ -52,6 +52,8 @@ _SIGNATURES = {
                                                      _sz, _vp]),
     "svoo_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
     "svoo_attention_density": (ctypes.c_int, [_SP, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp]),
+    "svoo_microbench_mfma_bf16": (ctypes.c_int, [_i32, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
+    "svoo_microbench_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -350,6 +352,26 @@ def attention_density(q, k, tau=0.95, scale=None, rows=None, want_passes=False):
                                        _ptr(prefix_len), _ptr(density), _ptr(passes), _stream())
     _run(st, "svoo_attention_density")
     return (prefix_len, density, passes) if want_passes else (prefix_len, density)
+
+
+def microbench_mfma_bf16(sink, iters, random_operands=True):
+    """svoo_microbench_mfma_bf16 on sink.numel() / 256 workgroups.  Returns the launch's flop count."""
+    _check(sink, torch.float32, None, "sink")
+    flops = ctypes.c_double(0.0)
+    st = _lib().svoo_microbench_mfma_bf16(sink.numel() // 256, iters, int(random_operands), _ptr(sink),
+                                          ctypes.byref(flops), _stream())
+    _run(st, "svoo_microbench_mfma_bf16")
+    return flops.value
+
+
+def microbench_copy(src, dst):
+    """svoo_microbench_copy of the whole of src into dst.  Returns the bytes moved (read + written)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("src and dst differ in size")
+    st = _lib().svoo_microbench_copy(_ptr(src), _ptr(dst), nbytes, _stream())
+    _run(st, "svoo_microbench_copy")
+    return 2 * nbytes
 
 
 class Layer:

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "svoo.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(svoo_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(svoo_[a-z0-9_]+)\s*\(", text)))
 
 
 @pytest.fixture(scope="module")
@@ -121,6 +121,12 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
     assert lib.svoo_kmeans(sp, fake, 2000, fake, null, 2, fake, fake, fake, null, fake, ws_bytes, null) == INVALID
     assert lib.svoo_kmeans(sp, fake, 16, fake, null, 0, fake, fake, fake, null, fake, ws_bytes, null) == INVALID
     assert lib.svoo_kmeans(sp, fake, 16, fake, null, 2, fake, fake, fake, null, fake, 64, null) == TOO_SMALL
+    assert lib.svoo_microbench_mfma_bf16(0, 10, 1, fake, null, null) == INVALID
+    assert lib.svoo_microbench_mfma_bf16(8, 0, 1, fake, null, null) == INVALID
+    assert lib.svoo_microbench_mfma_bf16(8, 10, 1, null, null, null) == INVALID
+    assert lib.svoo_microbench_copy(fake, ctypes.c_void_p(0x2000), 24, null) == INVALID       # not a multiple of 16
+    assert lib.svoo_microbench_copy(odd, ctypes.c_void_p(0x2000), 32, null) == INVALID
+    assert lib.svoo_microbench_copy(fake, null, 32, null) == INVALID
 
 
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):

@@ -54,6 +54,7 @@ def parse_args():
                         "launch then also carries the row moves)")
     p.add_argument("--no-density", action="store_true", help="skip the offline attention-density measurement")
     p.add_argument("--density-rows", type=int, default=2048, help="sampled query rows per head for the density")
+    p.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of one layer step")
     p.add_argument("--no-microbench", action="store_true",
                    help="skip the matrix-core and copy microbenchmarks the fractions are also quoted against")
     p.add_argument("--no-partitioner-comparison", action="store_true",
@@ -210,6 +211,41 @@ def main():
         dense_ms = d0.elapsed_time(d1) / args.dense_reps
         print(f"[bench] dense svoo_attn: {dense_ms:.1f} ms", file=sys.stderr, flush=True)
 
+    # ---- the same layer step recorded once into a HIP graph and replayed (every call only enqueues kernels)
+    graph_leg = None
+    if not args.no_graph:
+        x, kp = inputs[0], keep_dev[0]
+
+        def plain_step():
+            layer_obj.run(x["q"], x["k"], x["v"], x["init_q_idx"], x["init_k_idx"], cfg.iters, kp, tau, theta, scale)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            plain_step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        want = layer_obj.out.clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            plain_step()
+        torch.cuda.synchronize()
+        times = {}
+        for name, fn in (("eager_ms", plain_step), ("replay_ms", graph.replay)):
+            fn()
+            torch.cuda.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record()
+            for _ in range(5):
+                fn()
+            g1.record()
+            torch.cuda.synchronize()
+            times[name] = round(g0.elapsed_time(g1) / 5, 3)
+        graph_leg = {"keep": round(float(keeps[0]), 4), **times,
+                     "replay_equals_eager": bool(torch.equal(layer_obj.out, want))}
+        del graph
+        print(f"[bench] HIP graph: {graph_leg}", file=sys.stderr, flush=True)
+
     # ---- clustering reuse (paragraph "Clustering Reuse"; the paper re-clusters every 20 diffusion steps)
     reuse = None
     if args.reuse > 1:
@@ -356,6 +392,8 @@ def main():
         result["partitioner_comparison"] = comparison
     if density is not None:
         result["offline_density"] = density
+    if graph_leg is not None:
+        result["hip_graph"] = graph_leg
     if measured is not None:
         tensor_bytes = cfg.heads * cfg.n * cfg.d * (2 if cfg.dtype == "bf16" else 4)
         perm_ms, unperm_ms = float(step_ms[:, 1].mean()), float(step_ms[:, 4].mean())

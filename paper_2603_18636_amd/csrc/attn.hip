@@ -304,12 +304,18 @@ sparse_attn_bf16_kernel(AttnArgs a) {
 
     // ---- which rows / which keys this wave works on.
     // Normal tile: wave w owns rows 32w .. 32w+31 and every key.  Tile with at most half the rows
-    // (the last tile of a query block, often): the waves split the KEYS instead -- wave pair g =
-    // w / 2 takes the g-th 32-key block of every tile for rows 32 (w % 2) .., and the two partial
-    // results are merged at the end -- so that a short tile costs half the time, not all of it.
-    const bool split = NW >= 4 && ti.qn <= BM / 2;
-    const int kgrp = split ? wave / (NW / 2) : 0;
-    const int rwave = split ? wave % (NW / 2) : wave;
+    // (the last tile of a query block, often): the waves split the KEYS instead -- wave group g
+    // takes the (g % 2)-th 32-key block of every tile for rows 32 (w % row_waves) .., and the
+    // partial results are merged at the end -- so that a short tile costs about half the time, not
+    // all of it.  With 4 waves and at most 32 rows there are four groups: groups 0, 1 take the two
+    // blocks of the even tiles, groups 2, 3 those of the odd tiles.
+    const int kgroups = (NW >= 4 && ti.qn <= BM / 2) ? ((NW == 4 && ti.qn <= BM / 4) ? 4 : 2) : 1;
+    const bool split = kgroups > 1;
+    const int row_waves = NW / kgroups;
+    const int kgrp = wave / row_waves;
+    const int rwave = wave % row_waves;
+    const bool alternate = kgroups == 4;     // this wave computes every other tile only
+    const int parity = kgrp / 2;
     // ---- Q fragments: query row (rwave, j), contraction elements 16c + 8h .. +7
     const int qrow = 32 * rwave + j;
     const bool qvalid = qrow < ti.qn;
@@ -345,7 +351,7 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     // key-split waves read "their" 32-key block of every tile: fold its offset into the addresses.
     // The offsets are turned into absolute LDS byte addresses here, once, so that inside the loop a
     // read is "address register + immediate" with nothing left to add.
-    const int kb_off = 32 * kgrp;
+    const int kb_off = 32 * (kgrp % 2);
     const int k_base = (int)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)k_lds;
     const int v_base = (int)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)v_lds;
 #pragma unroll
@@ -549,7 +555,7 @@ sparse_attn_bf16_kernel(AttnArgs a) {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();    // tile kt has landed for every wave; everyone is done with tile kt-1's buffer
             if (kt + NBUF - 1 < n_tiles) issue_prepared((BUF + NBUF - 1) % NBUF);
-            if (wave_active) tile_body(bufc, modec, kt);
+            if (wave_active && (!alternate || (kt & 1) == parity)) tile_body(bufc, modec, kt);
             if (kt + NBUF < n_tiles) prepare_tile(kt + NBUF);
         };
         for (int kt = 0; kt < n_tiles; kt += NBUF) {
@@ -574,9 +580,11 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     }
     __syncthreads();   // all waves are done with the K/V tiles
     if (split) {
-        // wave pair 1 parks (O, m, l) in LDS; wave pair 0 folds it into its own partial result
-        float* park = (float*)smem + rwave * ((16 * DB + 2) * 64);
-        if (kgrp == 1 && wave_active) {
+        // groups 1.. park (O, m, l) in LDS; group 0 folds them into its own partial result
+        constexpr int PARK = (16 * DB + 2) * 64;
+        static_assert((NW == 4 ? 3 : NW / 2) * PARK * 4 <= AttnLds<D, NBUF>::BYTES, "parked partials exceed the LDS");
+        if (kgrp > 0 && wave_active) {
+            float* park = (float*)smem + ((kgrp - 1) * row_waves + rwave) * PARK;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -586,16 +594,19 @@ sparse_attn_bf16_kernel(AttnArgs a) {
         }
         __syncthreads();
         if (kgrp == 0 && wave_active) {
-            const float m_b = park[(16 * DB) * 64 + lane], l_b = park[(16 * DB + 1) * 64 + lane];
-            const float m_new = fmaxf(m_used, m_b);
-            const float sa = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
-            const float sb = m_b == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_b - m_new) * c2);
+            for (int g = 1; g < kgroups; ++g) {
+                const float* park = (const float*)smem + ((g - 1) * row_waves + rwave) * PARK;
+                const float m_b = park[(16 * DB) * 64 + lane], l_b = park[(16 * DB + 1) * 64 + lane];
+                const float m_new = fmaxf(m_used, m_b);
+                const float sa = m_used == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_used - m_new) * c2);
+                const float sb = m_b == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_b - m_new) * c2);
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] = o[db][v] * sa + park[(16 * db + v) * 64 + lane] * sb;
-            ltot = ltot * sa + l_b * sb;
-            m_used = m_new;
+                    for (int v = 0; v < 16; ++v) o[db][v] = o[db][v] * sa + park[(16 * db + v) * 64 + lane] * sb;
+                ltot = ltot * sa + l_b * sb;
+                m_used = m_new;
+            }
         }
         __syncthreads();   // the staging below reuses the same LDS
     }

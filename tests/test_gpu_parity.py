@@ -238,6 +238,47 @@ def test_sparse_attn_matches_oracle_random_mask(dtype, d):
     H.assert_attn_close(out, ref, dtype, "sparse random mask")
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_sparse_attn_short_query_blocks_and_short_key_streams(d):
+    """Query blocks of 1 .. 200 rows against key streams of one, two, three and many 64-key tiles:
+    every way the waves of a workgroup divide a tile (by rows, by keys in two or four groups, groups
+    that see no tile at all) ends in the same softmax."""
+    rng = np.random.default_rng(7 + d)
+    q_sizes = [1, 17, 32, 33, 64, 65, 96, 97, 128, 129, 200, 31]
+    k_sizes = [40, 60, 90, 5, 640, 64]          # kept streams of 5, 40, 64, 65, 90, 104, 150, 195, 640, 704, 899 keys
+    kept = [[0], [1, 2], [0, 1, 2, 3], [4, 5], [3], [5], [0, 5], [2], [1, 3], [4], [0, 1, 2, 3, 4, 5], [0]]
+    n = max(sum(q_sizes), sum(k_sizes))
+    q_sizes[-2] += n - sum(q_sizes)
+    k_sizes[4] += n - sum(k_sizes)
+    kq, kk = len(q_sizes), len(k_sizes)
+    lq = rng.permutation(np.repeat(np.arange(kq), q_sizes)).astype(np.int32)
+    lk = rng.permutation(np.repeat(np.arange(kk), k_sizes)).astype(np.int32)
+    q = (1.5 * rng.standard_normal((n, d))).astype(np.float32)
+    k = (1.5 * rng.standard_normal((n, d))).astype(np.float32)
+    v = rng.standard_normal((n, d)).astype(np.float32)
+    qd, kd, vd = (H.to_dev(x[None], "bf16") for x in (q, k, v))
+    q, k, v = (H.to_np(x)[0].astype(np.float64) for x in (qd, kd, vd))     # the bf16-rounded values
+    mask = np.zeros((kq, kk), dtype=bool)
+    lst = np.full((kq, kk), -1, dtype=np.int32)
+    for r, cols in enumerate(kept):
+        mask[r, cols] = True
+        lst[r, :len(cols)] = cols
+    cnt = mask.sum(1).astype(np.int32)
+    scale = H.scale_of(d)
+    perm_q, q_off, (qs,) = svoo.permute(H.to_dev(lq[None]), kq, [qd])
+    perm_k, k_off, (ks, vs) = svoo.permute(H.to_dev(lk[None]), kk, [kd, vd])
+    o_sorted, lse = svoo.block_sparse_attn(qs, ks, vs, q_off, k_off, H.to_dev(cnt[None]), H.to_dev(lst[None]), scale,
+                                           want_lse=True)
+    out = H.to_np(svoo.unpermute(o_sorted, perm_q))[0]
+    ref = so.sparse_attention(q, k, v, lq, lk, mask, scale)
+    H.assert_attn_close(out, ref, "bf16", "short blocks")
+    lse = H.to_np(lse)[0][np.argsort(H.to_np(perm_q)[0], kind="stable")]     # sorted position -> token order
+    s = scale * (q @ k.T)
+    s[~mask[lq][:, lk]] = -np.inf
+    lse_ref = np.log(np.exp(s - s.max(1, keepdims=True)).sum(1)) + s.max(1)
+    np.testing.assert_allclose(lse, lse_ref, atol=2e-2)
+
+
 def test_sparse_attn_no_kept_block_writes_zeros():
     h = small_cfg1_head(dtype="bf16")
     n = h["q"].shape[0]

@@ -76,8 +76,14 @@ __global__ void f32_to_f64_kernel(const float* __restrict__ src, double* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
-// Small batched float64 GEMM with arbitrary strides: C[m, n] = sum_k A(m, k) * B(k, n).
-// 32 x 32 output tile per workgroup, 2 x 2 per thread, contraction in steps of 16 in index order.
+// Small batched float64 GEMM with arbitrary strides: C[m, n] = sum_k A(m, k) * B(k, n), on the
+// float64 matrix instruction (v_mfma_f64_16x16x4_f64): one wave per 16 x 32 output tile, operands
+// straight from global memory (the matrices are a few hundred KB and sit in L2) -- lane (i, kq) =
+// (lane % 16, lane / 16) supplies A(m0 + i, k) and B(k, n0 + i), B(k, n0 + 16 + i) for the two
+// contraction indices k = k0 + 2 kq, k0 + 2 kq + 1 of a block of 8 (any assignment of indices to
+// the instruction's four contraction slots is valid as long as A and B agree); accumulator v of
+// the lane holds C(m0 + kq + 4 v, n0 + i).  AK2 / BK2: the lane's two A / B values are adjacent
+// in memory and 16-byte aligned, so one load fetches both.
 // Used for Pbar = C_own C_opp^T, W = Pbar^ C_opp and G = C_opp^T C_opp (all tiny next to the
 // token-sized work).
 // ---------------------------------------------------------------------------------------------
@@ -91,45 +97,68 @@ struct GemmArgs {
     const int32_t* only_if;   // nullable: per-batch flag; the batch is skipped when it is 0
 };
 
-__global__ void __launch_bounds__(256) gemm_f64_kernel(GemmArgs g) {
-    __shared__ double as[16][33];
-    __shared__ double bs[16][33];
+typedef __attribute__((ext_vector_type(4))) double f64x4;
+
+template <bool K2>
+__device__ __forceinline__ void load_k_pair(const double* __restrict__ row, int k, int k_end, int sk, double& v0,
+                                            double& v1) {
+    if (K2 && k + 1 < k_end) {
+        const double2 t = *(const double2*)(row + k);
+        v0 = t.x;
+        v1 = t.y;
+    } else {
+        v0 = k < k_end ? row[(size_t)k * sk] : 0.0;
+        v1 = k + 1 < k_end ? row[(size_t)(k + 1) * sk] : 0.0;
+    }
+}
+
+template <bool AK2, bool BK2>
+__global__ void __launch_bounds__(64) gemm_f64_kernel(GemmArgs g) {
     if (g.only_if && g.only_if[blockIdx.z] == 0) return;
     const double* a = g.a + (size_t)blockIdx.z * g.a_batch;
     const double* b = g.b + (size_t)blockIdx.z * g.b_batch;
     double* c = g.c + (size_t)blockIdx.z * g.c_batch;
-    const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
-    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-    double acc[2][2] = {{0, 0}, {0, 0}};
-    for (int k0 = 0; k0 < g.k; k0 += 16) {
-        for (int e = threadIdx.x; e < 512; e += 256) {
-            const int kk = e % 16, r = e / 16;
-            const int m = m0 + r, n = n0 + r, k = k0 + kk;
-            as[kk][r] = (m < g.m && k < g.k) ? a[(size_t)m * g.a_sm + (size_t)k * g.a_sk] : 0.0;
-            bs[kk][r] = (n < g.n && k < g.k) ? b[(size_t)k * g.b_sk + (size_t)n * g.b_sn] : 0.0;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            const double a0 = as[kk][ty * 2], a1 = as[kk][ty * 2 + 1];
-            const double b0 = bs[kk][tx * 2], b1 = bs[kk][tx * 2 + 1];
-            acc[0][0] = fma(a0, b0, acc[0][0]);
-            acc[0][1] = fma(a0, b1, acc[0][1]);
-            acc[1][0] = fma(a1, b0, acc[1][0]);
-            acc[1][1] = fma(a1, b1, acc[1][1]);
-        }
-        __syncthreads();
+    const int lane = threadIdx.x, i = lane % 16, kq = lane / 16;
+    const int m0 = blockIdx.y * 16, n0 = blockIdx.x * 32;
+    // rows / columns past the edge read row / column 0: their products only reach outputs that are not stored
+    const double* ap = a + (size_t)(m0 + i < g.m ? m0 + i : 0) * g.a_sm;
+    const double* bp0 = b + (size_t)(n0 + i < g.n ? n0 + i : 0) * g.b_sn;
+    const double* bp1 = b + (size_t)(n0 + 16 + i < g.n ? n0 + 16 + i : 0) * g.b_sn;
+    f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+    for (int k0 = 0; k0 < g.k; k0 += 8) {
+        const int k = k0 + 2 * kq;
+        double a0, a1, b00, b01, b10, b11;
+        load_k_pair<AK2>(ap, k, g.k, g.a_sk, a0, a1);
+        load_k_pair<BK2>(bp0, k, g.k, g.b_sk, b00, b01);
+        load_k_pair<BK2>(bp1, k, g.k, g.b_sk, b10, b11);
+        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b00, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b10, acc1, 0, 0, 0);
+        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b01, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b11, acc1, 0, 0, 0);
     }
-    for (int i = 0; i < 2; ++i)
-        for (int j = 0; j < 2; ++j) {
-            const int m = m0 + ty * 2 + i, n = n0 + tx * 2 + j;
-            if (m < g.m && n < g.n) c[(size_t)m * g.n + n] = acc[i][j];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int m = m0 + kq + 4 * v;
+        if (m < g.m) {
+            if (n0 + i < g.n) c[(size_t)m * g.n + n0 + i] = acc0[v];
+            if (n0 + 16 + i < g.n) c[(size_t)m * g.n + n0 + 16 + i] = acc1[v];
         }
+    }
 }
 
 static void launch_gemm(const GemmArgs& g, int batch, hipStream_t stream) {
-    dim3 grid((g.n + 31) / 32, (g.m + 31) / 32, batch);
-    hipLaunchKernelGGL(gemm_f64_kernel, grid, dim3(256), 0, stream, g);
+    dim3 grid((g.n + 31) / 32, (g.m + 15) / 16, batch);
+    const bool ak2 = g.a_sk == 1 && g.a_sm % 2 == 0 && g.a_batch % 2 == 0 && ((uintptr_t)g.a & 15) == 0;
+    const bool bk2 = g.b_sk == 1 && g.b_sn % 2 == 0 && g.b_batch % 2 == 0 && ((uintptr_t)g.b & 15) == 0;
+    if (ak2 && bk2)
+        hipLaunchKernelGGL((gemm_f64_kernel<true, true>), grid, dim3(64), 0, stream, g);
+    else if (ak2)
+        hipLaunchKernelGGL((gemm_f64_kernel<true, false>), grid, dim3(64), 0, stream, g);
+    else if (bk2)
+        hipLaunchKernelGGL((gemm_f64_kernel<false, true>), grid, dim3(64), 0, stream, g);
+    else
+        hipLaunchKernelGGL((gemm_f64_kernel<false, false>), grid, dim3(64), 0, stream, g);
 }
 
 // Row-wise L2 normalisation of Pbar [bh, k_own, k_opp] in place; b_j and the degenerate flag.
@@ -182,12 +211,13 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
     int32_t* tok = red_j + 64 * 16;    // [64]
 
     const int b = blockIdx.y;
-    const int t0 = blockIdx.x * 64;
     const int count = list ? list_count[b] : n;
-    if (t0 >= count) return;
     // nx^2 is only consumed by slices with a degenerate anchor unless the caller forces it
     if (MODE == MODE_QUADFORM && !force_general && flags[b] == 0) return;
     const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+    // one tile per workgroup when the grid covers every tile; a smaller grid walks the tiles
+    for (int t0 = blockIdx.x * 64; t0 < count; t0 += gridDim.x * 64) {
+    __syncthreads();   // the previous tile's last LDS reads are done
     if (tid < 64) {
         const int p = t0 + tid;
         tok[tid] = p < count ? (list ? list[(size_t)b * n + p] : p) : -1;
@@ -295,6 +325,7 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
             quad_out[(size_t)b * n + tok[tid]] = s;
         }
     }
+    }   // tile loop
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -385,7 +416,11 @@ static void launch_token_tile(const T* x, const double* bmat, int rows_b, const 
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)token_tile_lds<D>()) != hipSuccess)
         return;   // the failure stays recorded as HIP's last error: the caller's launch_status() reports it
-    dim3 grid((n + 63) / 64, bh);
+    // The quadratic form is skipped by every slice without a degenerate anchor unless it is forced:
+    // a small grid that walks the tiles keeps that common case at a few microseconds.
+    const int tiles = (n + 63) / 64;
+    const bool mostly_skipped = MODE == MODE_QUADFORM && !force_general;
+    dim3 grid(mostly_skipped && tiles > 64 ? 64 : tiles, bh);
     hipLaunchKernelGGL(kern, grid, dim3(256), token_tile_lds<D>(), stream, x, bmat, rows_b, bterm, flags, nx2, list,
                        list_count, force_general, labels, quad_out, n);
 }

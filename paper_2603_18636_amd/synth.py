@@ -25,6 +25,7 @@ from __future__ import annotations
 
 import dataclasses
 import math
+import threading
 from typing import Dict, List, Optional, Tuple
 
 import numpy as np
@@ -103,6 +104,17 @@ def layer_keeps(cfg: Config) -> np.ndarray:
     return rng.uniform(lo, hi, size=cfg.n_layers).astype(np.float32)
 
 
+# Heads may be drawn by several threads at once (make_layer).  Concurrent calls into the BLAS behind
+# numpy's matmul have returned corrupted rows now and then, so every matrix product takes this lock
+# (the products are a small part of the work: the normal draws and sin/cos dominate).
+_MATMUL_LOCK = threading.Lock()
+
+
+def _mm(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    with _MATMUL_LOCK:
+        return a @ b
+
+
 def grid_positions(grid: Tuple[int, int, int]) -> np.ndarray:
     """Normalised (t, h, w) position of every token, token index = (t*H + h)*W + w."""
     t, h, w = grid
@@ -145,9 +157,9 @@ def logit_row_variance(q: np.ndarray, k: np.ndarray) -> float:
     n, d = q.shape
     mu = k.mean(axis=0, keepdims=True)
     kc = k - mu
-    sigma_k = kc.T @ kc / k.shape[0]
-    gram_q = q.T @ q / n
-    return float(np.trace(sigma_k @ gram_q) / d)
+    sigma_k = _mm(kc.T, kc) / k.shape[0]
+    gram_q = _mm(q.T, q) / n
+    return float(np.trace(_mm(sigma_k, gram_q)) / d)
 
 
 def sample_distinct(rng: np.random.Generator, n: int, k: int) -> np.ndarray:
@@ -183,10 +195,10 @@ def make_head(cfg: Config, layer: int, head: int, grid: Optional[Tuple[int, int,
     freqs = rng.standard_normal((8, 3)) * 2.0
     f_q = rng.standard_normal((16, d)) / 4.0
     f_k = rng.standard_normal((16, d)) / 4.0
-    ang = 2.0 * math.pi * (u @ freqs.T)
+    ang = 2.0 * math.pi * _mm(u, freqs.T)
     phi = np.concatenate([np.sin(ang), np.cos(ang)], axis=1)
-    q = (z @ m_q)[region] + phi @ f_q + 0.3 * rng.standard_normal((n, d))
-    k = (z @ m_k)[region] + phi @ f_k + 0.3 * rng.standard_normal((n, d))
+    q = _mm(z, m_q)[region] + _mm(phi, f_q) + 0.3 * rng.standard_normal((n, d))
+    k = _mm(z, m_k)[region] + _mm(phi, f_k) + 0.3 * rng.standard_normal((n, d))
     v = rng.standard_normal((n, d))
     var = logit_row_variance(q, k)
     gamma = (9.0 / var) ** 0.25

@@ -94,6 +94,24 @@ def test_assign_degenerate_anchor_and_zero_tokens():
     H.compare_labels(got, ref, best, second)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_assign_degenerate_anchor_in_one_of_two_slices_many_tiles(dtype):
+    """6,240 tokens (more 64-token tiles than the grid of the usually skipped quadratic-form launch),
+    two slices: one with an all-zero own-side centroid and zero tokens, one ordinary."""
+    h = [small_cfg1_head(head=b, grid=(4, 30, 52), dtype=dtype) for b in (0, 1)]
+    k = [x["k"].copy() for x in h]
+    k[0][4100:4130] = 0.0
+    k[0][77] = 0.0
+    ck = [k[b][h[b]["init_k_idx"]].astype(np.float32) for b in (0, 1)]
+    ck[0][5] = 0.0
+    cq = [h[b]["q"][h[b]["init_q_idx"]].astype(np.float32) for b in (0, 1)]
+    got = H.to_np(svoo.assign(H.to_dev(np.stack(k), dtype), H.to_dev(np.stack(ck)), H.to_dev(np.stack(cq))))
+    for b in (0, 1):
+        ref, best, second = H.oracle_assign(k[b], ck[b], cq[b])
+        H.compare_labels(got[b], ref, best, second)
+    assert (got[0][4100:4130] == 5).all() and got[0][77] == 5
+
+
 # ------------------------------------------------------------------------------------------ cocluster
 def run_cocluster_case(h, iters, dtype, want_objective=False):
     q, k = h["q"], h["k"]

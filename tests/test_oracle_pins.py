@@ -341,6 +341,11 @@ def test_generator_is_deterministic_and_dtype_exact():
     assert len(set(a["init_q_idx"].tolist())) == 8
     x = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -1.00390625], dtype=np.float32)
     assert synth.round_to_bf16(x).tolist() == [1.0, 1.015625, -1.0]
+    # heads drawn by a thread pool are the heads drawn one by one
+    kw = dict(grid=(5, 12, 16), n_seeds=8, kq=8, kk=8)
+    serial = synth.make_layer(synth.CONFIGS[1], 0, heads=list(range(6)), workers=1, **kw)
+    pooled = synth.make_layer(synth.CONFIGS[1], 0, heads=list(range(6)), workers=6, **kw)
+    assert all((serial[x] == pooled[x]).all() for x in serial)
 
 
 # ---------------------------------------------------------------------------- independent k-means

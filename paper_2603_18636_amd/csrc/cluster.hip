@@ -125,17 +125,22 @@ __global__ void __launch_bounds__(64) gemm_f64_kernel(GemmArgs g) {
     const double* bp0 = b + (size_t)(n0 + i < g.n ? n0 + i : 0) * g.b_sn;
     const double* bp1 = b + (size_t)(n0 + 16 + i < g.n ? n0 + 16 + i : 0) * g.b_sn;
     f64x4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
-    for (int k0 = 0; k0 < g.k; k0 += 8) {
-        const int k = k0 + 2 * kq;
-        double a0, a1, b00, b01, b10, b11;
-        load_k_pair<AK2>(ap, k, g.k, g.a_sk, a0, a1);
-        load_k_pair<BK2>(bp0, k, g.k, g.b_sk, b00, b01);
-        load_k_pair<BK2>(bp1, k, g.k, g.b_sk, b10, b11);
-        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b00, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b10, acc1, 0, 0, 0);
-        acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b01, acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b11, acc1, 0, 0, 0);
+    for (int k00 = 0; k00 < g.k; k00 += 32) {     // four blocks of 8 per trip: their loads are in flight together
+        double a0[4], a1[4], b00[4], b01[4], b10[4], b11[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = k00 + 8 * u + 2 * kq;       // past the end: zeros
+            load_k_pair<AK2>(ap, k, g.k, g.a_sk, a0[u], a1[u]);
+            load_k_pair<BK2>(bp0, k, g.k, g.b_sk, b00[u], b01[u]);
+            load_k_pair<BK2>(bp1, k, g.k, g.b_sk, b10[u], b11[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[u], b00[u], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0[u], b10[u], acc1, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[u], b01[u], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1[u], b11[u], acc1, 0, 0, 0);
+        }
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
@@ -159,32 +164,6 @@ static void launch_gemm(const GemmArgs& g, int batch, hipStream_t stream) {
         hipLaunchKernelGGL((gemm_f64_kernel<false, true>), grid, dim3(64), 0, stream, g);
     else
         hipLaunchKernelGGL((gemm_f64_kernel<false, false>), grid, dim3(64), 0, stream, g);
-}
-
-// Row-wise L2 normalisation of Pbar [bh, k_own, k_opp] in place; b_j and the degenerate flag.
-__global__ void __launch_bounds__(256)
-normalize_anchor_rows_kernel(double* __restrict__ pbar, double* __restrict__ bterm, int32_t* __restrict__ flags,
-                             int k_own, int k_opp) {
-    __shared__ double red[256];
-    const int b = blockIdx.y, j = blockIdx.x, t = threadIdx.x;
-    double* row = pbar + ((size_t)b * k_own + j) * k_opp;
-    double s = 0.0;
-    for (int c = t; c < k_opp; c += 256) s = fma(row[c], row[c], s);
-    red[t] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if (t < w) red[t] += red[t + w];
-        __syncthreads();
-    }
-    const double nrm = sqrt(red[0]);
-    const double div = nrm > NORM_FLOOR ? nrm : NORM_FLOOR;
-    for (int c = t; c < k_opp; c += 256) row[c] = row[c] / div;
-    if (t == 0) {
-        const bool degenerate = !(nrm >= NORM_FLOOR);
-        const double r = nrm / NORM_FLOOR;
-        bterm[(size_t)b * k_own + j] = degenerate ? r * r : 1.0;
-        if (degenerate) atomicOr(&flags[b], 1);
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -506,6 +485,156 @@ split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint1
     }
 }
 
+// Everything the assignment needs from the centroids, for 16 own-side centroids per workgroup:
+//   P    = C_own[16 rows] C_opp^T          (float64 matrix instruction, tiles kept in LDS)
+//   P^   = rows of P divided by max(||row||, floor);  b_j, degenerate flag
+//   W    = P^ C_opp                        (16 x D)
+//   and, for bf16 tokens, W's two-term bf16 split, W^T and the slice's largest row norm.
+// One launch instead of GEMM, normalisation, GEMM and split; the K_own x K_opp matrix never leaves
+// the chip.  Wave w owns the column tiles w, w + 4, .. of each product and rows 4w .. 4w+3 of the
+// row-wise steps.  Lane (i, kq) = (lane % 16, lane / 16) feeds row / column i and the contraction
+// indices k0 + 2 kq, k0 + 2 kq + 1 of a block of 8; accumulator v holds row kq + 4 v, column i.
+template <int D>
+__global__ void __launch_bounds__(256)
+anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_opp, int k_own, int k_opp,
+                double* __restrict__ w64, double* __restrict__ bterm, int32_t* __restrict__ flags,
+                uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo, double* __restrict__ wt,
+                int32_t* __restrict__ wmax_bits) {
+    extern __shared__ __attribute__((aligned(16))) double anchor_lds[];
+    __shared__ float wave_max[4];
+    const int pitch = ((k_opp + 31) / 32) * 32 + 2;     // even: 16-byte aligned pairs; columns past k_opp hold 0
+    double* ps = anchor_lds;                            // [16][pitch]
+    double* wtile = anchor_lds + 16 * pitch;            // [16][D + 2]
+    const int b = blockIdx.y, row0 = blockIdx.x * 16;
+    const int wave = threadIdx.x / 64, lane = threadIdx.x % 64, i = lane % 16, kq = lane / 16;
+    const double* co = c_own + (size_t)b * k_own * D;
+    const double* cp = c_opp + (size_t)b * k_opp * D;
+
+    // ---- P tile
+    {
+        const double* arow = co + (size_t)(row0 + i < k_own ? row0 + i : k_own - 1) * D + 2 * kq;
+        double2 a[D / 8];
+#pragma unroll
+        for (int kb = 0; kb < D / 8; ++kb) a[kb] = *(const double2*)(arow + 8 * kb);
+        for (int ct = wave; ct * 16 < k_opp; ct += 4) {
+            const int n = ct * 16 + i;
+            const double* brow = cp + (size_t)(n < k_opp ? n : k_opp - 1) * D + 2 * kq;
+            f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kb = 0; kb < D / 8; ++kb) {
+                const double2 bb = *(const double2*)(brow + 8 * kb);
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[kb].x, bb.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a[kb].y, bb.y, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) ps[(kq + 4 * v) * pitch + n] = n < k_opp ? acc[v] : 0.0;
+        }
+        const int filled = ((k_opp + 15) / 16) * 16, rest = pitch - filled;
+        for (int e = threadIdx.x; e < 16 * rest; e += 256) ps[(e / rest) * pitch + filled + e % rest] = 0.0;
+    }
+    __syncthreads();
+    // ---- row-wise L2 normalisation, b_j, degenerate flag
+    for (int r = 0; r < 4; ++r) {
+        double* row = ps + (4 * wave + r) * pitch;
+        double sq = 0.0;
+        for (int c = lane; c < k_opp; c += 64) sq = fma(row[c], row[c], sq);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
+        const double nrm = sqrt(sq);
+        const double div = nrm > NORM_FLOOR ? nrm : NORM_FLOOR;
+        for (int c = lane; c < k_opp; c += 64) row[c] = row[c] / div;
+        const int j = row0 + 4 * wave + r;
+        if (lane == 0 && j < k_own) {
+            const bool degenerate = !(nrm >= NORM_FLOOR);
+            const double q = nrm / NORM_FLOOR;
+            bterm[(size_t)b * k_own + j] = degenerate ? q * q : 1.0;
+            if (degenerate) atomicOr(&flags[b], 1);
+        }
+    }
+    __syncthreads();
+    // ---- W tile = P^ C_opp
+    {
+        constexpr int NT = D / 64;                      // column tiles per wave
+        f64x4 acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+        const double* prow = ps + i * pitch + 2 * kq;
+        for (int k00 = 0; k00 < k_opp; k00 += 32) {   // four blocks of 8 per trip: their loads are in flight together
+            double b0[4][NT], b1[4][NT];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int k = k00 + 8 * u + 2 * kq;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int col = (wave + 4 * t) * 16 + i;
+                    b0[u][t] = k < k_opp ? cp[(size_t)k * D + col] : 0.0;
+                    b1[u][t] = k + 1 < k_opp ? cp[(size_t)(k + 1) * D + col] : 0.0;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const double2 pa = *(const double2*)(prow + k00 + 8 * u);
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(pa.x, b0[u][t], acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(pa.y, b1[u][t], acc[t], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) wtile[(kq + 4 * v) * (D + 2) + (wave + 4 * t) * 16 + i] = acc[t][v];
+    }
+    __syncthreads();
+    // ---- outputs: W, and for the matrix-core pre-filter its bf16 split, W^T and the largest row norm
+    float mx = 0.f;
+    for (int r = 0; r < 4; ++r) {
+        const int j = row0 + 4 * wave + r;
+        if (j >= k_own) break;                         // uniform per wave
+        double sq = 0.0;
+        for (int t = lane; t < D; t += 64) {
+            const size_t o = ((size_t)b * k_own + j) * D + t;
+            const double v = wtile[(4 * wave + r) * (D + 2) + t];
+            w64[o] = v;
+            if (whi) {
+                const uint16_t hb = f32_to_bf16((float)v);
+                whi[o] = hb;
+                wlo[o] = f32_to_bf16((float)(v - (double)bf16_to_f32(hb)));
+                wt[((size_t)b * D + t) * k_own + j] = v;
+            }
+            sq = fma(v, v, sq);
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
+        float nrm = (float)sqrt(sq);
+        nrm = nrm * 1.0000002f + 1e-37f;   // round up
+        if (!(nrm < 3.0e38f)) nrm = 3.0e38f;
+        mx = fmaxf(mx, nrm);
+    }
+    if (whi) {
+        if (lane == 0) wave_max[wave] = mx;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const float m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+            atomicMax(&wmax_bits[b], __float_as_int(m));
+        }
+    }
+}
+
+template <int D>
+static void launch_anchor_w(const double* c_own, const double* c_opp, int k_own, int k_opp, int bh, double* w64,
+                            double* bterm, int32_t* flags, uint16_t* whi, uint16_t* wlo, double* wt,
+                            int32_t* wmax_bits, hipStream_t stream) {
+    auto kern = anchor_w_kernel<D>;
+    const int pitch = ((k_opp + 31) / 32) * 32 + 2;
+    const int lds = (16 * pitch + 16 * (D + 2)) * (int)sizeof(double);
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+        return;   // stays recorded as HIP's last error: the caller's launch_status() reports it
+    hipLaunchKernelGGL(kern, dim3((k_own + 15) / 16, bh), dim3(256), lds, stream, c_own, c_opp, k_own, k_opp, w64, bterm,
+                       flags, whi, wlo, wt, wmax_bits);
+}
+
 // BIAS: score_j = <x, W_j> - half_sq[j] (k-means on raw rows: W = C, half_sq = ||c_j||^2 / 2, one
 // float per centroid, slices padded to a multiple of 32 entries); the margin then also covers the
 // float32 rounding of the bias and of the subtraction.
@@ -824,7 +953,7 @@ kmeans_inertia_terms_kernel(const T* __restrict__ x, const double* __restrict__ 
 // host side
 // ---------------------------------------------------------------------------------------------
 struct ClusterWs {
-    double *c64q, *c64k, *w64, *wt64, *pbar, *gram, *bterm, *nx2, *terms;
+    double *c64q, *c64k, *w64, *wt64, *gram, *bterm, *nx2, *terms;
     uint16_t *whi, *wlo;
     float* half_sq;
     int32_t *flags, *wmax_bits, *list_count, *list, *perm, *offsets, *chunk_hist;
@@ -839,7 +968,6 @@ static ClusterWs carve_cluster_ws(const svoo_shape* s, void* ws) {
     w.c64k = c.take<double>(bh * s->kk * s->d);
     w.w64 = c.take<double>(bh * kmax * s->d);
     w.wt64 = c.take<double>(bh * kmax * s->d);
-    w.pbar = c.take<double>(bh * (size_t)s->kq * s->kk);
     w.gram = c.take<double>(bh * (size_t)s->d * s->d);
     w.bterm = c.take<double>(bh * kmax);
     w.nx2 = c.take<double>(bh * (size_t)s->n);
@@ -867,16 +995,18 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
     const int d = s->d, bh = s->bh;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((3 * bh + 255) / 256), dim3(256), 0, stream, w.flags, 0,
                        (size_t)3 * bh);
-    // Pbar[j, c] = <c_own_j, c_opp_c>
-    GemmArgs g1 = {c_own, c_opp, w.pbar, k_own, k_opp, d, (long long)k_own * d, (long long)k_opp * d,
-                   (long long)k_own * k_opp, d, 1, 1, d, nullptr};
-    launch_gemm(g1, bh, stream);
-    hipLaunchKernelGGL(normalize_anchor_rows_kernel, dim3(k_own, bh), dim3(256), 0, stream, w.pbar, w.bterm, w.flags,
-                       k_own, k_opp);
-    // W[j, :] = sum_c Pbar^[j, c] * c_opp[c, :]
-    GemmArgs g2 = {w.pbar, c_opp, w.w64, k_own, d, k_opp, (long long)k_own * k_opp, (long long)k_opp * d,
-                   (long long)k_own * d, k_opp, 1, d, 1, nullptr};
-    launch_gemm(g2, bh, stream);
+    // W = Norm(C_own C_opp^T) C_opp with b_j and the degenerate flags; for bf16 tokens also the split of W,
+    // its transpose and the largest row norm for the matrix-core pre-filter
+    {
+        const bool bf16 = s->dtype == SVOO_BF16;
+        uint16_t* whi = bf16 ? w.whi : nullptr;
+        if (d == 128)
+            launch_anchor_w<128>(c_own, c_opp, k_own, k_opp, bh, w.w64, w.bterm, w.flags, whi, w.wlo, w.wt64,
+                                 w.wmax_bits, stream);
+        else
+            launch_anchor_w<64>(c_own, c_opp, k_own, k_opp, bh, w.w64, w.bterm, w.flags, whi, w.wlo, w.wt64,
+                                w.wmax_bits, stream);
+    }
     // G[a, b] = sum_c c_opp[c, a] * c_opp[c, b]
     // (only slices with a degenerate anchor need it, unless the objective is wanted)
     GemmArgs g3 = {c_opp, c_opp, w.gram, d, d, k_opp, (long long)k_opp * d, (long long)k_opp * d, (long long)d * d,
@@ -888,15 +1018,11 @@ static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, c
                                        nullptr, w.nx2, stream);
     if (s->dtype == SVOO_BF16) {
         // matrix-core pre-filter decides the clear cases; float64 decides the queued rest
-        dim3 sgrid((k_own + 15) / 16, bh), agrid((s->n + 255) / 256, bh);
+        dim3 agrid((s->n + 255) / 256, bh);
         if (d == 128) {
-            hipLaunchKernelGGL(split_w_kernel<128>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wt64,
-                               w.wmax_bits, k_own);
             hipLaunchKernelGGL((assign_mfma_kernel<128, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         } else {
-            hipLaunchKernelGGL(split_w_kernel<64>, sgrid, dim3(256), 0, stream, w.w64, w.whi, w.wlo, w.wt64,
-                               w.wmax_bits, k_own);
             hipLaunchKernelGGL((assign_mfma_kernel<64, false>), agrid, dim3(256), 0, stream, (const uint16_t*)x, w.whi,
                                w.wlo, w.wmax_bits, w.flags, nullptr, labels, w.list, w.list_count, s->n, k_own);
         }

@@ -491,17 +491,19 @@ split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint1
 //   W    = P^ C_opp                        (16 x D)
 //   and, for bf16 tokens, W's two-term bf16 split, W^T and the slice's largest row norm.
 // One launch instead of GEMM, normalisation, GEMM and split; the K_own x K_opp matrix never leaves
-// the chip.  Wave w owns the column tiles w, w + 4, .. of each product and rows 4w .. 4w+3 of the
-// row-wise steps.  Lane (i, kq) = (lane % 16, lane / 16) feeds row / column i and the contraction
+// the chip.  Eight waves: wave w owns the column tiles w, w + 8, .. of each product and two rows of
+// the row-wise steps.  Lane (i, kq) = (lane % 16, lane / 16) feeds row / column i and the contraction
 // indices k0 + 2 kq, k0 + 2 kq + 1 of a block of 8; accumulator v holds row kq + 4 v, column i.
+#define ANCHOR_WAVES 8
 template <int D>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * ANCHOR_WAVES)
 anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_opp, int k_own, int k_opp,
                 double* __restrict__ w64, double* __restrict__ bterm, int32_t* __restrict__ flags,
                 uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo, double* __restrict__ wt,
                 int32_t* __restrict__ wmax_bits) {
     extern __shared__ __attribute__((aligned(16))) double anchor_lds[];
-    __shared__ float wave_max[4];
+    constexpr int NW = ANCHOR_WAVES, RPW = 16 / NW;      // rows per wave in the row-wise steps
+    __shared__ float wave_max[NW];
     const int pitch = ((k_opp + 31) / 32) * 32 + 2;     // even: 16-byte aligned pairs; columns past k_opp hold 0
     double* ps = anchor_lds;                            // [16][pitch]
     double* wtile = anchor_lds + 16 * pitch;            // [16][D + 2]
@@ -516,7 +518,7 @@ anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_o
         double2 a[D / 8];
 #pragma unroll
         for (int kb = 0; kb < D / 8; ++kb) a[kb] = *(const double2*)(arow + 8 * kb);
-        for (int ct = wave; ct * 16 < k_opp; ct += 4) {
+        for (int ct = wave; ct * 16 < k_opp; ct += NW) {
             const int n = ct * 16 + i;
             const double* brow = cp + (size_t)(n < k_opp ? n : k_opp - 1) * D + 2 * kq;
             f64x4 acc = {0.0, 0.0, 0.0, 0.0};
@@ -530,12 +532,12 @@ anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_o
             for (int v = 0; v < 4; ++v) ps[(kq + 4 * v) * pitch + n] = n < k_opp ? acc[v] : 0.0;
         }
         const int filled = ((k_opp + 15) / 16) * 16, rest = pitch - filled;
-        for (int e = threadIdx.x; e < 16 * rest; e += 256) ps[(e / rest) * pitch + filled + e % rest] = 0.0;
+        for (int e = threadIdx.x; e < 16 * rest; e += 64 * NW) ps[(e / rest) * pitch + filled + e % rest] = 0.0;
     }
     __syncthreads();
     // ---- row-wise L2 normalisation, b_j, degenerate flag
-    for (int r = 0; r < 4; ++r) {
-        double* row = ps + (4 * wave + r) * pitch;
+    for (int r = 0; r < RPW; ++r) {
+        double* row = ps + (RPW * wave + r) * pitch;
         double sq = 0.0;
         for (int c = lane; c < k_opp; c += 64) sq = fma(row[c], row[c], sq);
 #pragma unroll
@@ -543,7 +545,7 @@ anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_o
         const double nrm = sqrt(sq);
         const double div = nrm > NORM_FLOOR ? nrm : NORM_FLOOR;
         for (int c = lane; c < k_opp; c += 64) row[c] = row[c] / div;
-        const int j = row0 + 4 * wave + r;
+        const int j = row0 + RPW * wave + r;
         if (lane == 0 && j < k_own) {
             const bool degenerate = !(nrm >= NORM_FLOOR);
             const double q = nrm / NORM_FLOOR;
@@ -552,50 +554,67 @@ anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_o
         }
     }
     __syncthreads();
-    // ---- W tile = P^ C_opp
+    // ---- W tile = P^ C_opp: wave w owns the 16-column tiles w, w + NW, ..; the next trip's operands are
+    // requested before the current trip's matrix instructions
     {
-        constexpr int NT = D / 64;                      // column tiles per wave
-        f64x4 acc[NT];
+        constexpr int TILES = D / 16, NT = (TILES + NW - 1) / NW;
+        if (wave < TILES) {
+            f64x4 acc[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
-        const double* prow = ps + i * pitch + 2 * kq;
-        for (int k00 = 0; k00 < k_opp; k00 += 32) {   // four blocks of 8 per trip: their loads are in flight together
+            for (int t = 0; t < NT; ++t) acc[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+            const double* prow = ps + i * pitch + 2 * kq;
             double b0[4][NT], b1[4][NT];
+            auto fetch = [&](int k00, double (&f0)[4][NT], double (&f1)[4][NT]) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int k = k00 + 8 * u + 2 * kq;
+                for (int u = 0; u < 4; ++u) {
+                    const int k = k00 + 8 * u + 2 * kq;
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int col = (wave + 4 * t) * 16 + i;
-                    b0[u][t] = k < k_opp ? cp[(size_t)k * D + col] : 0.0;
-                    b1[u][t] = k + 1 < k_opp ? cp[(size_t)(k + 1) * D + col] : 0.0;
+                    for (int t = 0; t < NT; ++t) {
+                        const int col = (wave + NW * t) * 16 + i;
+                        const bool cv = wave + NW * t < TILES;
+                        f0[u][t] = cv && k < k_opp ? cp[(size_t)k * D + col] : 0.0;
+                        f1[u][t] = cv && k + 1 < k_opp ? cp[(size_t)(k + 1) * D + col] : 0.0;
+                    }
                 }
+            };
+            fetch(0, b0, b1);
+            for (int k00 = 0; k00 < k_opp; k00 += 32) {
+                double n0[4][NT], n1[4][NT];
+                fetch(k00 + 32, n0, n1);          // past the end: zeros, no loads
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const double2 pa = *(const double2*)(prow + k00 + 8 * u);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(pa.x, b0[u][t], acc[t], 0, 0, 0);
+                        acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(pa.y, b1[u][t], acc[t], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        b0[u][t] = n0[u][t];
+                        b1[u][t] = n1[u][t];
+                    }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const double2 pa = *(const double2*)(prow + k00 + 8 * u);
+            for (int t = 0; t < NT; ++t)
+                if (wave + NW * t < TILES)
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(pa.x, b0[u][t], acc[t], 0, 0, 0);
-                    acc[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(pa.y, b1[u][t], acc[t], 0, 0, 0);
-                }
-            }
+                    for (int v = 0; v < 4; ++v) wtile[(kq + 4 * v) * (D + 2) + (wave + NW * t) * 16 + i] = acc[t][v];
         }
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) wtile[(kq + 4 * v) * (D + 2) + (wave + 4 * t) * 16 + i] = acc[t][v];
     }
     __syncthreads();
     // ---- outputs: W, and for the matrix-core pre-filter its bf16 split, W^T and the largest row norm
     float mx = 0.f;
-    for (int r = 0; r < 4; ++r) {
-        const int j = row0 + 4 * wave + r;
+    for (int r = 0; r < RPW; ++r) {
+        const int j = row0 + RPW * wave + r;
         if (j >= k_own) break;                         // uniform per wave
         double sq = 0.0;
         for (int t = lane; t < D; t += 64) {
             const size_t o = ((size_t)b * k_own + j) * D + t;
-            const double v = wtile[(4 * wave + r) * (D + 2) + t];
+            const double v = wtile[(RPW * wave + r) * (D + 2) + t];
             w64[o] = v;
             if (whi) {
                 const uint16_t hb = f32_to_bf16((float)v);
@@ -616,8 +635,10 @@ anchor_w_kernel(const double* __restrict__ c_own, const double* __restrict__ c_o
         if (lane == 0) wave_max[wave] = mx;
         __syncthreads();
         if (threadIdx.x == 0) {
-            const float m = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
-            atomicMax(&wmax_bits[b], __float_as_int(m));
+            float m = wave_max[0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) m = fmaxf(m, wave_max[w]);
+            atomicMax(&wmax_bits[b], __float_as_int(m));   // non-negative floats order like their bit patterns
         }
     }
 }
@@ -631,8 +652,8 @@ static void launch_anchor_w(const double* c_own, const double* c_opp, int k_own,
     const int lds = (16 * pitch + 16 * (D + 2)) * (int)sizeof(double);
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return;   // stays recorded as HIP's last error: the caller's launch_status() reports it
-    hipLaunchKernelGGL(kern, dim3((k_own + 15) / 16, bh), dim3(256), lds, stream, c_own, c_opp, k_own, k_opp, w64, bterm,
-                       flags, whi, wlo, wt, wmax_bits);
+    hipLaunchKernelGGL(kern, dim3((k_own + 15) / 16, bh), dim3(64 * ANCHOR_WAVES), lds, stream, c_own, c_opp, k_own,
+                       k_opp, w64, bterm, flags, whi, wlo, wt, wmax_bits);
 }
 
 // BIAS: score_j = <x, W_j> - half_sq[j] (k-means on raw rows: W = C, half_sq = ||c_j||^2 / 2, one

@@ -7,7 +7,8 @@
 //   scan     one workgroup per slice: per bin, exclusive prefix over chunks (bin-major, chunk-minor
 //            order = stable order), bin totals = cluster sizes, exclusive scan of totals = offsets
 //   scatter  one wave per chunk walks its tokens 64 at a time in index order; lanes with equal
-//            labels are ranked with ballots, so equal labels keep ascending token order
+//            labels find each other with one ballot per label bit and are ranked by lane, so equal
+//            labels keep ascending token order
 #include "common.h"
 
 #define SORT_CHUNK 512
@@ -63,8 +64,10 @@ sort_scan_kernel(int32_t* __restrict__ chunk_hist, int32_t* __restrict__ offsets
     const int c0 = g * cpg, c1 = (c0 + cpg < nchunks) ? c0 + cpg : nchunks;
     int32_t* h = chunk_hist + (size_t)b * nchunks * k;
     int sum = 0;
-    if (live)
+    if (live) {
+#pragma unroll 8
         for (int c = c0; c < c1; ++c) sum += h[(size_t)c * k + j];
+    }
     tot[tid] = live ? sum : 0;
     __syncthreads();
     int base = 0, total = 0;
@@ -75,6 +78,7 @@ sort_scan_kernel(int32_t* __restrict__ chunk_hist, int32_t* __restrict__ offsets
             total += v;
         }
         int running = base;
+#pragma unroll 8
         for (int c = c0; c < c1; ++c) {
             const int v = h[(size_t)c * k + j];
             h[(size_t)c * k + j] = running;
@@ -118,24 +122,34 @@ sort_scatter_kernel(const int32_t* __restrict__ labels, const int32_t* __restric
     int32_t* out = perm + (size_t)b * n;
     const int start = chunk * SORT_CHUNK;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int label_bits = 0;
+    while ((1 << label_bits) < k) ++label_bits;
+    int mine[SORT_CHUNK / SVOO_WAVE];     // all of the lane's labels requested at once
+#pragma unroll
     for (int g = 0; g < SORT_CHUNK / SVOO_WAVE; ++g) {
         const int i = start + g * SVOO_WAVE + lane;
-        const bool valid = active && i < n;
-        const int label = valid ? clamp_label(lab[i], k) : -1;
-        unsigned long long remaining = __ballot(valid);
-        while (remaining) {  // wave-uniform: one pass per distinct label among the 64 tokens
-            const int leader = __ffsll((long long)remaining) - 1;
-            const int c0 = __shfl(label, leader);
-            const unsigned long long same = __ballot(label == c0);
-            if (label == c0) {
-                const int pos = cnt[c0] + __popcll(same & lt_mask);
-                out[pos] = i;
-            }
-            __builtin_amdgcn_wave_barrier();
-            if (lane == leader) cnt[c0] += __popcll(same);
-            remaining &= ~same;
+        mine[g] = (active && i < n) ? clamp_label(lab[i], k) : -1;
+    }
+#pragma unroll
+    for (int g = 0; g < SORT_CHUNK / SVOO_WAVE; ++g) {
+        const int i = start + g * SVOO_WAVE + lane;
+        const int label = mine[g];
+        const bool valid = label >= 0;
+        // lanes with my label: one ballot per label bit, no loop over the distinct labels
+        unsigned long long same = __ballot(valid);
+        for (int bit = 0; bit < label_bits; ++bit) {
+            const bool set = (label >> bit) & 1;
+            const unsigned long long bal = __ballot(set);
+            same &= set ? bal : ~bal;
         }
-        __syncthreads();
+        int first = 0;
+        if (valid) {
+            first = cnt[label];
+            out[first + __popcll(same & lt_mask)] = i;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (valid && (same & lt_mask) == 0) cnt[label] = first + __popcll(same);   // lowest lane of each label
+        __builtin_amdgcn_wave_barrier();   // cnt belongs to this wave alone: no workgroup barrier needed
     }
 }
 

@@ -108,3 +108,15 @@ def test_paper_hyperparameters_asymmetric_clusters():
     cfg = synth.CONFIGS[5]
     *_, stats = run_and_check(cfg, [0, 7], cfg.keep, 0.95, 0.1, n_rows=200)
     print(f"paper hyper-parameters: {stats}")
+
+
+def test_maximum_cluster_counts_both_sides():
+    """K_q = K_k = 1024 (the largest the library takes) on the 480p grid: query blocks of ~32 rows, so
+    nearly every attention tile is a short one whose waves divide the keys, and every mask row ranks
+    1024 blocks."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.CONFIGS[1], name="max clusters", kq=1024, kk=1024, iters=2, n_seeds=512)
+    data, dev, layer, out, stats = run_and_check(cfg, [0, 3], 0.2, 0.95, 0.1, n_rows=200)
+    counts = H.to_np(layer.counts_q)
+    print(f"max clusters: {stats}; query cluster sizes min {counts.min()} mean {counts.mean():.1f} max {counts.max()}")
+    assert counts.mean() == cfg.n / 1024

@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # Bytes past L2 per svoo_block_sparse_attn launch on configs[2], from the rocprofv3 --pmc passes summarised
 # in profiles/sparse_attn_config2_pmc.txt (FETCH_SIZE scaled by 1.97, the factor a copy of known size gives,
 # plus WRITE_SIZE); measured offline, at the keep ratios of the first two layers of the sweep.
-MEASURED_TRAFFIC_BYTES = {2: 9.7e10}
+MEASURED_TRAFFIC_BYTES = {2: 9.8e10}
 STEP_NAMES = ("cocluster", "permute", "block_mask", "sparse_attn", "unpermute")
 
 

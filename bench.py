@@ -66,8 +66,8 @@ def parse_args():
 def cpu_baseline(cfg, data, keep, tau, theta, scale, kept_flops_layer):
     """The fp64 oracle, as it stands, on a bounded sample: head 0 of the first resident layer, ONE
     co-clustering iteration (both half-steps at full N), the block mask, and block-sparse attention
-    for 16384 evenly spaced query rows (9-25 s in all, depending on the host).  Scaled to a whole layer
-    (x iterations, x N/16384 rows, x heads) and expressed in the metric's unit."""
+    for 24576 evenly spaced query rows (10-40 s in all, depending on the host).  Scaled to a whole layer
+    (x iterations, x N/24576 rows, x heads) and expressed in the metric's unit."""
     from oracle import svoo_oracle as so
     try:
         from threadpoolctl import threadpool_info
@@ -83,7 +83,7 @@ def cpu_baseline(cfg, data, keep, tau, theta, scale, kept_flops_layer):
     mask = so.block_mask(cc["cq"].astype(np.float32).astype(np.float64), cc["ck"].astype(np.float32).astype(np.float64),
                          cc["counts_q"], cc["counts_k"], keep, tau, theta, scale)
     t_mask = time.perf_counter() - t0
-    rows = np.linspace(0, n - 1, min(n, 16384)).astype(np.int64)
+    rows = np.linspace(0, n - 1, min(n, 24576)).astype(np.int64)
     t0 = time.perf_counter()
     so.sparse_attention(q, k, v, cc["labels_q"], cc["labels_k"], mask, scale, rows=rows)
     t_attn = time.perf_counter() - t0

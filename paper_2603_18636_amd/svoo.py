@@ -321,6 +321,31 @@ def block_sparse_attn(q_sorted, k_sorted, v_sorted, q_offsets, k_offsets, block_
     return (out, lse) if want_lse else out
 
 
+def block_sparse_attn_tokens(q, q_perm, k_sorted, v_sorted, q_offsets, k_offsets, block_count, block_list, scale: float,
+                             want_lse=False, out=None, ws=None):
+    """svoo_block_sparse_attn_tokens: q and out in token order, moved through q_perm by the kernel.
+    Returns out (and lse, in token order, if asked)."""
+    bh, n, d = q.shape
+    kq, kk = q_offsets.shape[1] - 1, k_offsets.shape[1] - 1
+    shape = make_shape(q, kq, kk)
+    for name, t in (("q", q), ("k_sorted", k_sorted), ("v_sorted", v_sorted)):
+        _check(t, q.dtype, (bh, n, d), name)
+    _check(q_perm, torch.int32, (bh, n), "q_perm")
+    _check(q_offsets, torch.int32, (bh, kq + 1), "q_offsets")
+    _check(k_offsets, torch.int32, (bh, kk + 1), "k_offsets")
+    _check(block_count, torch.int32, (bh, kq), "block_count")
+    _check(block_list, torch.int32, (bh, kq, kk), "block_list")
+    out = torch.empty_like(q) if out is None else out
+    _check(out, q.dtype, (bh, n, d), "out")
+    lse = torch.empty((bh, n), dtype=torch.float32, device=q.device) if want_lse else None
+    ws = workspace(shape, q.device) if ws is None else ws
+    st = _lib().svoo_block_sparse_attn_tokens(ctypes.byref(shape), _ptr(q), _ptr(q_perm), _ptr(k_sorted), _ptr(v_sorted),
+                                              _ptr(q_offsets), _ptr(k_offsets), _ptr(block_count), _ptr(block_list),
+                                              scale, _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream())
+    _run(st, "svoo_block_sparse_attn_tokens")
+    return (out, lse) if want_lse else out
+
+
 def attn(q, k, v, scale: float, want_lse=False, out=None, ws=None):
     """svoo_attn: dense softmax(scale * q k^T) v."""
     bh, n, d = q.shape

@@ -1,0 +1,105 @@
+"""Seeded random small shapes: every combination of sizes a caller may pass must give the oracle's
+result, not only the shapes of the workloads (n below one tile, one key, more clusters than fit a
+tile, empty clusters, every dtype / head dimension)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import svoo_oracle as so
+from paper_2603_18636_amd import svoo, synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+DIVERGED = []
+
+
+def random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    d = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "f32"]))
+    n = int(rng.choice([1, 2, 31, 33, 63, 64, 65, 127, 129, 200, 257, 400, 700]))
+    kq = int(rng.integers(1, min(n, 12) + 1))
+    kk = int(rng.integers(1, min(n, 14) + 1))
+    bh = int(rng.integers(1, 4))
+    q = (1.5 * rng.standard_normal((bh, n, d))).astype(np.float32)
+    k = (1.5 * rng.standard_normal((bh, n, d))).astype(np.float32)
+    v = rng.standard_normal((bh, n, d)).astype(np.float32)
+    if dtype == "bf16":
+        q, k, v = (synth.round_to_bf16(x) for x in (q, k, v))
+    return rng, d, dtype, n, kq, kk, bh, q, k, v
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_sparse_attention_random_layout(seed):
+    rng, d, dtype, n, kq, kk, bh, q, k, v = random_case(seed)
+    # labels with some clusters possibly empty
+    lq = rng.integers(0, kq, (bh, n)).astype(np.int32)
+    lk = rng.integers(0, kk, (bh, n)).astype(np.int32)
+    if kk > 2:
+        lk[lk == 1] = 0                               # key cluster 1 is empty in every slice
+    mask = rng.random((bh, kq, kk)) < 0.5
+    cnt = np.zeros((bh, kq), dtype=np.int32)
+    lst = np.full((bh, kq, kk), -1, dtype=np.int32)
+    for b in range(bh):
+        nk = np.bincount(lk[b], minlength=kk)
+        mask[b][:, nk == 0] = False
+        for r in range(kq):
+            ids = np.nonzero(mask[b, r])[0]
+            cnt[b, r] = len(ids)
+            lst[b, r, :len(ids)] = ids
+    scale = H.scale_of(d)
+    qd, kd, vd = (H.to_dev(x, dtype) for x in (q, k, v))
+    perm_q, q_off, (qs,) = svoo.permute(H.to_dev(lq), kq, [qd])
+    perm_k, k_off, (ks, vs) = svoo.permute(H.to_dev(lk), kk, [kd, vd])
+    o_sorted = svoo.block_sparse_attn(qs, ks, vs, q_off, k_off, H.to_dev(cnt), H.to_dev(lst), scale)
+    out = H.to_np(svoo.unpermute(o_sorted, perm_q))
+    fused = H.to_np(svoo.block_sparse_attn_tokens(qd, perm_q, ks, vs, q_off, k_off, H.to_dev(cnt), H.to_dev(lst), scale))
+    assert np.array_equal(out, fused)
+    for b in range(bh):
+        ref = so.sparse_attention(q[b], k[b], v[b], lq[b], lk[b], mask[b], scale)
+        H.assert_attn_close(out[b], ref, dtype, f"seed {seed} slice {b} (n={n}, kq={kq}, kk={kk}, d={d}, {dtype})")
+        p_ref, o_ref = so.stable_permutation(lq[b], kq)
+        assert (H.to_np(perm_q)[b] == p_ref).all() and (H.to_np(q_off)[b] == o_ref).all()
+
+
+@pytest.mark.parametrize("seed", range(24, 40))
+def test_layer_random_small_shapes(seed):
+    """Whole layer (co-clustering, mask, attention) on random small shapes against the oracle."""
+    rng, d, dtype, n, kq, kk, bh, q, k, v = random_case(seed)
+    iters = int(rng.integers(1, 4))
+    keep = float(np.float32(rng.uniform(0.1, 1.0)))
+    tau, theta = float(np.float32(rng.choice([0.9, 0.95, 1.0]))), float(np.float32(rng.choice([0.0, 0.1, 0.5])))
+    init_q = np.stack([synth.sample_distinct(rng, n, kq) for _ in range(bh)])
+    init_k = np.stack([synth.sample_distinct(rng, n, kk) for _ in range(bh)])
+    layer = svoo.Layer(bh, n, d, H.torch_dtype(dtype), kq, kk, H.DEV)
+    out = layer.run(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), H.to_dev(init_q), H.to_dev(init_k),
+                    iters, H.to_dev(np.full(bh, keep, dtype=np.float32)), tau, theta)
+    torch.cuda.synchronize()
+    out = H.to_np(out)
+    scale = H.scale_of(d)
+    for b in range(bh):
+        cc = so.cocluster(q[b], k[b], init_q[b], init_k[b], iters)
+        same = (H.to_np(layer.labels_q)[b] == cc["labels_q"]).all() and (H.to_np(layer.labels_k)[b] == cc["labels_k"]).all()
+        if not same:
+            # a label may only differ at a near-tie of the assignment; then the rest of the run legitimately
+            # diverges (the step-wise tests cover that case) -- report it, it must stay rare
+            print(f"seed {seed} slice {b}: labels differ from the oracle's, slice skipped")
+            DIVERGED.append((seed, b))
+            continue
+        lq, lk = cc["labels_q"], cc["labels_k"]
+        cq32, ck32 = H.to_np(layer.cq)[b], H.to_np(layer.ck)[b]
+        np.testing.assert_allclose(cq32, cc["cq"], rtol=2e-6, atol=1e-6)
+        mask = so.block_mask(cq32.astype(np.float64), ck32.astype(np.float64), cc["counts_q"], cc["counts_k"],
+                             np.float32(keep), tau, theta, scale)
+        margins = so.selection_margins(cq32.astype(np.float64), ck32.astype(np.float64), cc["counts_q"], cc["counts_k"],
+                                       np.float32(keep), tau, theta, scale)
+        gpu_mask = H.to_np(layer.bitmap)[b].astype(bool)
+        ok = margins >= H.NEAR_TIE
+        assert (gpu_mask[ok] == mask[ok]).all()
+        ref = so.sparse_attention(q[b], k[b], v[b], lq, lk, gpu_mask, scale)
+        H.assert_attn_close(out[b], ref, dtype, f"seed {seed} slice {b} (n={n}, kq={kq}, kk={kk}, d={d}, {dtype})")
+
+
+def test_random_layers_rarely_diverge():
+    assert len(DIVERGED) <= 1, DIVERGED

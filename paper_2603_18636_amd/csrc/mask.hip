@@ -217,7 +217,7 @@ block_mask_kernel(const double* __restrict__ abar, const int32_t* __restrict__ c
 
     // compact the kept ids in ascending order: thread t owns ids t, t+256, ...; do it per stripe
     int base = 0;
-    for (int u = 0; u < MASK_PER_THREAD; ++u) {
+    for (int u = 0; u < MASK_PER_THREAD && u * MASK_THREADS < kk; ++u) {   // stripes past kk hold nothing
         const int j = t + u * MASK_THREADS;
         const int kept = (j < kk && rank[u] >= 0 && rank[u] < n_keep) ? 1 : 0;
         if (j < kk && bitmap) bitmap[row_off + j] = (uint8_t)kept;

@@ -84,8 +84,8 @@ __global__ void f32_to_f64_kernel(const float* __restrict__ src, double* __restr
 // the instruction's four contraction slots is valid as long as A and B agree); accumulator v of
 // the lane holds C(m0 + kq + 4 v, n0 + i).  AK2 / BK2: the lane's two A / B values are adjacent
 // in memory and 16-byte aligned, so one load fetches both.
-// Used for Pbar = C_own C_opp^T, W = Pbar^ C_opp and G = C_opp^T C_opp (all tiny next to the
-// token-sized work).
+// Used for G = C_opp^T C_opp (needed by slices with a degenerate anchor only; the other two small
+// products of a half-step are inside anchor_w_kernel).
 // ---------------------------------------------------------------------------------------------
 struct GemmArgs {
     const double* a;
@@ -449,7 +449,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 #endif
 #define FAST_EPS 3.1e-5f   // 2^-16 + 256 * 2^-24, twice the analytic bound for d <= 128
 
-// 16 rows per workgroup (one wave takes four of them), one atomic per workgroup; also writes W^T in float64
+// The split of a float64 score matrix for the pre-filter as a launch of its own (k-means, where W is the
+// centroid array itself): 16 rows per workgroup (one wave takes four of them), one atomic per workgroup;
+// also writes W^T in float64
 template <int D>
 __global__ void __launch_bounds__(256)
 split_w_kernel(const double* __restrict__ w64, uint16_t* __restrict__ whi, uint16_t* __restrict__ wlo,

@@ -1,5 +1,6 @@
 """Shared helpers of the GPU parity tests (marshalling and comparison only)."""
 import math
+import os
 
 import numpy as np
 import torch
@@ -78,3 +79,24 @@ def oracle_assign(x, c_own32, c_opp32):
 def scale_of(d):
     """1/sqrt(d) as the float32 that crosses the boundary."""
     return float(np.float32(1.0 / math.sqrt(d)))
+
+
+# the paper's intuition example for query-key coupling (fixture tests/golden/query_dependent_key_partition.txt)
+def load_coupling_example():
+    pts, parts = {}, {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "query_dependent_key_partition.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        name, rest = line.split(None, 1)
+        if name.startswith("partition_"):
+            parts[name[len("partition_"):]] = {frozenset(int(t) for t in grp.split()) for grp in rest.split("|")}
+        else:
+            pts[name] = [float(t) for t in rest.split()]
+    return pts, parts
+
+
+def embed(rows, d):
+    out = np.zeros((len(rows), d))
+    out[:, :2] = np.asarray(rows)
+    return out

@@ -112,6 +112,24 @@ def test_assign_degenerate_anchor_in_one_of_two_slices_many_tiles(dtype):
     assert (got[0][4100:4130] == 5).all() and got[0][77] == 5
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 64), ("f32", 128)])
+def test_key_partition_follows_the_query_anchors(dtype, d):
+    """The paper's intuition example (Sec. 4.2; fixture tests/golden/query_dependent_key_partition.txt) through
+    svoo_cocluster: four keys, query anchors like q1 or like q2, the two key blocks the paper names."""
+    pts, parts = H.load_coupling_example()
+    keys = H.embed([pts[f"k{i}"] for i in (1, 2, 3, 4)], d).astype(np.float32)
+    for which in ("q1", "q2"):
+        queries = H.embed([[s * c for c in pts[which]] for s in (1.0, 1.5, 0.5, 2.0)], d).astype(np.float32)
+        start = next(pair for pair in ((0, 2), (0, 1)) if not any(set(pair) <= g for g in parts[which]))
+        out = svoo.cocluster(H.to_dev(queries[None], dtype), H.to_dev(keys[None], dtype),
+                             H.to_dev(np.array([[0]], dtype=np.int32)), H.to_dev(np.array([start], dtype=np.int32)), 2)
+        labels_k = H.to_np(out["labels_k"])[0]
+        got = {frozenset(np.nonzero(labels_k == j)[0].tolist()) for j in range(2)}
+        assert got == parts[which], (which, got)
+        ref = so.cocluster(queries, keys, np.array([0], dtype=np.int32), np.array(start, dtype=np.int32), 2)
+        assert (labels_k == ref["labels_k"]).all() and (H.to_np(out["labels_q"])[0] == ref["labels_q"]).all()
+
+
 # ------------------------------------------------------------------------------------------ cocluster
 def run_cocluster_case(h, iters, dtype, want_objective=False):
     q, k = h["q"], h["k"]

@@ -3,6 +3,8 @@ forms, invariants and brute force on tiny inputs.  A plausible mistake in the or
 term, wrong sign or index, transposed operand, wrong centroid version) fails at least one."""
 import math
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -11,6 +13,7 @@ from sklearn.cluster import KMeans
 
 from oracle import svoo_oracle as so
 from paper_2603_18636_amd import synth
+from tests import helpers as H
 
 CFG0 = synth.CONFIGS[0]
 
@@ -515,3 +518,22 @@ def test_sparsity_schedule_is_the_gaussian_upper_quantile():
     assert abs(s - (1.0 - (mu + 1.6448536269514722 * sigma))) < 1e-12
     assert abs(gaussian.cdf((1.0 - s - mu) / sigma) - 0.95) < 1e-12
     assert so.sparsity_schedule(np.full(4, 0.4), 0.95) == pytest.approx(0.6)
+
+
+# ------------------------------------------------------------------- the paper's own small example
+def test_key_partition_depends_on_the_query_anchors():
+    """Sec. 4.2, the intuition example: the same four keys are split [k1,k2][k3,k4] when the anchors are
+    queries like q1 and [k1,k4][k2,k3] when they are like q2 (fixture tests/golden/query_dependent_key_partition.txt),
+    whereas a partition that ignores the queries (k-means on the keys) cannot change with them."""
+    pts, parts = H.load_coupling_example()
+    keys = H.embed([pts[f"k{i}"] for i in (1, 2, 3, 4)], 8)
+    for which in ("q1", "q2"):
+        queries = H.embed([pts[which], [1.5 * c for c in pts[which]], [0.5 * c for c in pts[which]]], 8)
+        for first_two in ((0, 2), (0, 1), (1, 3), (2, 3), (1, 2), (0, 3)):      # any two starting keys from different groups
+            if any(set(first_two) <= g for g in parts[which]):
+                continue
+            cc = so.cocluster(queries, keys, np.array([0], dtype=np.int32), np.array(first_two, dtype=np.int32), 2)
+            got = {frozenset(np.nonzero(cc["labels_k"] == j)[0].tolist()) for j in range(2)}
+            assert got == parts[which], (which, first_two, got)
+    a = so.kmeans(keys, np.array([0, 2], dtype=np.int32), 3)["labels"]
+    assert len(set(a.tolist())) <= 2      # and it is the same whatever the queries are: they are not an input

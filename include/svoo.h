@@ -76,6 +76,10 @@ int32_t svoo_version(void);
 /* Bytes of workspace sufficient for any call below with this shape (0 if the shape is invalid). */
 size_t svoo_workspace_bytes(const svoo_shape* shape);
 
+/* Bytes of workspace svoo_permute needs for labels with n_clusters bins (they may exceed shape->kq / kk; 0 if
+ * invalid).  svoo_workspace_bytes() covers n_clusters <= max(kq, kk). */
+size_t svoo_permute_workspace_bytes(const svoo_shape* shape, int32_t n_clusters);
+
 /*
  * Algorithm 1, bidirectional co-clustering.  For it = 1..iters:
  *   Step A  P = K C_q^T, Pbar = C_k C_q^T, both row-normalised (L2, floor 1e-12);
@@ -89,8 +93,9 @@ size_t svoo_workspace_bytes(const svoo_shape* shape);
  *
  * Outputs: labels_q/labels_k [bh, n]; cq [bh, kq, d], ck [bh, kk, d] float32 = exact means of the
  * returned labels (previous value for empty clusters); counts_q [bh, kq], counts_k [bh, kk].
- * objective (nullable) [bh, iters, 2] float64: sum_i ||P^_i - Pbar^_{L_i}||^2 at assignment time
- * of Step A (index 0) and Step B (index 1) -- a diagnostic, costs one extra pass per half-step.
+ * objective (nullable) [bh, iters, 2] float64 (sums of N float64 terms; float32 would lose the
+ * differences between iterations): sum_i ||P^_i - Pbar^_{L_i}||^2 at assignment time of Step A
+ * (index 0) and Step B (index 1) -- a diagnostic, costs one extra pass per half-step.
  * Arithmetic: assignment decisions are taken in float64 (a bf16 matrix-core pass only pre-filters
  * tokens whose best and second-best scores are far apart); centroid means are float64 sums in a
  * fixed order, carried in float64 between iterations and rounded to float32 on output.
@@ -181,7 +186,9 @@ int svoo_unpermute(const svoo_shape* shape, const void* src_sorted, const int32_
  *   w_j   = counts_k[j] * exp(a_j - max) / Z            size-weighted softmax over non-empty key blocks
  *   order = key blocks by w descending, equal weights by lower j
  *   m     = shortest prefix of `order` whose cumulative w >= tau  (all non-empty blocks if tau >= 1)
- *   b     = ceil(keep[b] * kk)                          keep = fraction of key blocks kept (budget s)
+ *   b     = ceil(keep[b] * kk)                          keep = fraction of key blocks kept (budget s); a product
+ *                                                       within 1e-6 kk of an integer counts as that integer
+ *                                                       (keep is a float32: 0.3f * 20 must give 6, not 7)
  *   kept  = first (keep[b] > theta ? min(m, b) : max(m, b)) of `order`, clamped to [1, #non-empty]
  * (the threshold-dependent rule of the selection paragraph; Recall(A_bar, tau) is read as m / kk).
  * All of it in float64 (A_bar is written to the workspace first, bh*kq*kk doubles).  keep [bh] float32
@@ -229,6 +236,17 @@ int svoo_block_sparse_attn_tokens(const svoo_shape* shape, const void* q, const 
 /* Dense attention out = softmax(scale * Q K^T) V in token order; kq, kk of the shape are ignored. */
 int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale,
               void* out, float* lse, void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * Attention recall of a block partition and mask (the measure of the paper's comparison of clustering
+ * strategies, read as the share of each query's dense softmax mass that falls on its kept keys):
+ *   recall[b, q_perm[b, p]] = exp(lse_kept_sorted[b, p] - lse_all[b, q_perm[b, p]])
+ * lse_kept_sorted [bh, n]: the lse output of svoo_block_sparse_attn (cluster order); lse_all [bh, n]:
+ * the lse output of svoo_attn (token order); q_perm [bh, n] the query permutation; recall [bh, n]
+ * float32 in token order.  A diagnostic, not a step of the layer.  shape->kq / kk are ignored.
+ */
+int svoo_row_recall(const svoo_shape* shape, const float* lse_kept_sorted, const float* lse_all,
+                    const int32_t* q_perm, float* recall, void* hip_stream);
 
 /*
  * Offline profiling: attention density (Sec. 4.1, offline profiling module, the equation defining

@@ -187,13 +187,29 @@ def block_weights(cq: np.ndarray, ck: np.ndarray, counts_k: np.ndarray, scale: f
     return e / z
 
 
+BUDGET_SNAP = 1e-6
+
+
+def budget_blocks(keep: float, kk: int) -> int:
+    """Number of key clusters the budget s allows: keep * K_k rounded up.  The keep ratio reaches
+    the library as a float32, so a decimal ratio whose product with K_k is an integer (0.3 * 20)
+    arrives a hair above it; a product within 1e-6 * K_k of an integer is therefore taken as that
+    integer before rounding up."""
+    x = float(keep) * kk
+    nearest = round(x)
+    if abs(x - nearest) <= BUDGET_SNAP * kk:
+        return int(nearest)
+    return int(math.ceil(x))
+
+
 def select_blocks(w_row: np.ndarray, live: np.ndarray, keep: float, tau: float, theta: float) -> np.ndarray:
     """Kept key clusters of one query cluster (boolean [K_k]) from its weight row.
 
     Order the live key clusters by weight, descending, equal weights by lower index first.  m =
     length of the shortest prefix whose cumulative weight reaches tau (all live clusters when tau
-    >= 1).  b = ceil(keep * K_k).  The number kept is min(m, b) if keep > theta, max(m, b)
-    otherwise (the threshold-dependent rule of the selection paragraph), clamped to [1, #live].
+    >= 1).  b = ceil(keep * K_k) (``budget_blocks``).  The number kept is min(m, b) if keep > theta,
+    max(m, b) otherwise (the threshold-dependent rule of the selection paragraph), clamped to
+    [1, #live].
     """
     kk = w_row.shape[0]
     n_live = int(live.sum())
@@ -208,7 +224,7 @@ def select_blocks(w_row: np.ndarray, live: np.ndarray, keep: float, tau: float, 
         csum = np.cumsum(w_row[order])
         reach = np.nonzero(csum >= tau)[0]
         m = int(reach[0]) + 1 if reach.size else n_live
-    b = int(math.ceil(float(keep) * kk))
+    b = budget_blocks(keep, kk)
     n_keep = min(m, b) if float(keep) > float(theta) else max(m, b)
     n_keep = max(1, min(n_keep, n_live))
     kept[order[:n_keep]] = True

@@ -17,7 +17,12 @@ extern "C" const char* svoo_status_string(int status) {
     }
 }
 
-extern "C" int32_t svoo_version(void) { return 100; }
+extern "C" int32_t svoo_version(void) { return 200; }
+
+extern "C" size_t svoo_permute_workspace_bytes(const svoo_shape* shape, int32_t n_clusters) {
+    if (check_shape(shape, false) != SVOO_OK || n_clusters < 1 || n_clusters > SVOO_MAX_K) return 0;
+    return align_up(sort_scratch_ints(shape->bh, shape->n, n_clusters) * sizeof(int32_t), 256);
+}
 
 extern "C" size_t svoo_workspace_bytes(const svoo_shape* shape) {
     if (check_shape(shape, true) != SVOO_OK) return 0;

@@ -204,14 +204,10 @@ __device__ __forceinline__ int stream_row(const int32_t* seg_start, const int32_
 //                    K/V traffic out of L2 per flop; a 4th buffer does not help.
 //   block-sparse   : 4 waves x 2 buffers, two workgroups per CU.  Query blocks are a few hundred
 //                    rows, so 128-row tiles waste fewer rows in the last tile of a block than 256.
-#ifndef SVOO_SPARSE_NW
 #define SVOO_SPARSE_NW 4
 #define SVOO_SPARSE_NBUF 2
-#endif
 #define DENSE_NW 8
-#ifndef DENSE_NBUF
 #define DENSE_NBUF 3
-#endif
 #define RESCALE_LOG2 8.0f   // the running max is only raised when it is exceeded by 2^8
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;
@@ -764,11 +760,10 @@ size_t attn_ws_bytes(const svoo_shape* s) {
 
 template <int D, int NW, int NBUF>
 static int launch_bf16(dim3 grid, const AttnArgs& a, hipStream_t stream) {
-    // more than 64 KB of dynamic LDS must be opted into per kernel
     auto kern = sparse_attn_bf16_kernel<D, NW, NBUF>;
     constexpr int lds_bytes = AttnLds<D, NBUF>::BYTES;
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
-        return SVOO_ERR_HIP;
+    static unsigned char opted_in[SVOO_MAX_DEVICES];
+    if (!opt_in_dynamic_lds((const void*)kern, lds_bytes, opted_in)) return SVOO_ERR_HIP;
     hipLaunchKernelGGL(kern, grid, dim3(64 * NW), lds_bytes, stream, a);
     return SVOO_OK;
 }
@@ -858,4 +853,27 @@ extern "C" int svoo_attn(const svoo_shape* shape, const void* q, const void* k, 
                        block_list, s.n, s.bh);
     AttnArgs a = {q, k, v, out, lse, offsets, offsets, block_count, block_list, nullptr, nullptr, s.n, 1, 1, scale};
     return launch_sparse(&s, a, tile_prefix, true, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Attention recall of a partition + block mask, per token, from the two log-sum-exp outputs:
+// the share of the dense softmax mass that falls on the kept keys is exp(LSE_kept - LSE_all).
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+row_recall_kernel(const float* __restrict__ lse_kept_sorted, const float* __restrict__ lse_all,
+                  const int32_t* __restrict__ q_perm, float* __restrict__ recall, int n) {
+    const int b = blockIdx.y, p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= n) return;
+    const int tok = clamp_row(q_perm[(size_t)b * n + p], n);
+    recall[(size_t)b * n + tok] = expf(lse_kept_sorted[(size_t)b * n + p] - lse_all[(size_t)b * n + tok]);
+}
+
+extern "C" int svoo_row_recall(const svoo_shape* shape, const float* lse_kept_sorted, const float* lse_all,
+                               const int32_t* q_perm, float* recall, void* hip_stream) {
+    int st = check_shape(shape, false);
+    if (st != SVOO_OK) return st;
+    if (!lse_kept_sorted || !lse_all || !q_perm || !recall || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(row_recall_kernel, dim3((shape->n + 255) / 256, shape->bh), dim3(256), 0,
+                       (hipStream_t)hip_stream, lse_kept_sorted, lse_all, q_perm, recall, shape->n);
+    return launch_status();
 }

@@ -391,9 +391,8 @@ static void launch_token_tile(const T* x, const double* bmat, int rows_b, const 
                               const double* nx2, const int32_t* list, const int32_t* list_count, int force_general,
                               int32_t* labels, double* quad_out, int bh, int n, hipStream_t stream) {
     auto kern = token_tile_kernel<T, D, MODE>;
-    // more than 64 KB of dynamic LDS has to be opted into per kernel (per device, so not cached here)
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)token_tile_lds<D>()) != hipSuccess)
+    static unsigned char opted_in[SVOO_MAX_DEVICES];
+    if (!opt_in_dynamic_lds((const void*)kern, (int)token_tile_lds<D>(), opted_in))
         return;   // the failure stays recorded as HIP's last error: the caller's launch_status() reports it
     // The quadratic form is skipped by every slice without a degenerate anchor unless it is forced:
     // a small grid that walks the tiles keeps that common case at a few microseconds.
@@ -444,9 +443,7 @@ static void dispatch_token_tile(const svoo_shape* s, const void* x, const double
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-#ifndef ASSIGN_LIST_WGS
 #define ASSIGN_LIST_WGS 256   // workgroups per slice that share the queue of undecided tokens
-#endif
 #define FAST_EPS 3.1e-5f   // 2^-16 + 256 * 2^-24, twice the analytic bound for d <= 128
 
 // The split of a float64 score matrix for the pre-filter as a launch of its own (k-means, where W is the
@@ -652,7 +649,10 @@ static void launch_anchor_w(const double* c_own, const double* c_opp, int k_own,
     auto kern = anchor_w_kernel<D>;
     const int pitch = ((k_opp + 31) / 32) * 32 + 2;
     const int lds = (16 * pitch + 16 * (D + 2)) * (int)sizeof(double);
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+    // the LDS need grows with k_opp: opt in once for the largest (k_opp = 1024) so that the flag holds for every call
+    constexpr int lds_max = (16 * (SVOO_MAX_K + 2) + 16 * (D + 2)) * (int)sizeof(double);
+    static unsigned char opted_in[SVOO_MAX_DEVICES];
+    if (!opt_in_dynamic_lds((const void*)kern, lds_max, opted_in))
         return;   // stays recorded as HIP's last error: the caller's launch_status() reports it
     hipLaunchKernelGGL(kern, dim3((k_own + 15) / 16, bh), dim3(64 * ANCHOR_WAVES), lds, stream, c_own, c_opp, k_own,
                        k_opp, w64, bterm, flags, whi, wlo, wt, wmax_bits);

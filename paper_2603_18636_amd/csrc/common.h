@@ -32,12 +32,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // then does not track an asynchronous LDS write and puts no "wait for every outstanding load" in
 // front of later LDS reads of OTHER buffers, which would undo the prefetch.  Ordering against the
 // reads of the buffer being filled is the caller's job (s_waitcnt vmcnt(..) followed by a barrier).
+// m0 is on the clobber list so that the compiler never carries a value of its own in m0 across the
+// statement (it treats m0 as reserved and says so with a warning, silenced here).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_global_to_lds_16(const void* gptr, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :
                  : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_addr))
-                 : "memory");
+                 : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
@@ -80,6 +85,19 @@ struct WsCarver {
 };
 
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? SVOO_OK : SVOO_ERR_HIP; }
+
+// Kernels that use more than 64 KB of dynamic LDS must opt in through a function attribute, once
+// per kernel and device.  `done` is a per-kernel-instantiation table (one flag per device ordinal);
+// racing first calls from two host threads both set the attribute, which is harmless.
+#define SVOO_MAX_DEVICES 64
+static inline bool opt_in_dynamic_lds(const void* kernel, int bytes, unsigned char (&done)[SVOO_MAX_DEVICES]) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (dev >= 0 && dev < SVOO_MAX_DEVICES && done[dev]) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    if (dev >= 0 && dev < SVOO_MAX_DEVICES) done[dev] = 1;
+    return true;
+}
 
 // ---------------------------------------------------------------------------------------------
 // internal entry points shared between translation units

@@ -6,7 +6,8 @@
 //   w_j  = n_j exp(a_j - max) / Z            softmax over non-empty key blocks, weighted by size
 //   rank_j = position of j in the order by descending w, equal weights by lower index (bitonic sort in LDS)
 //   m    = shortest sorted prefix with cumulative weight >= tau, summed sequentially in that order
-//   b    = ceil(keep * K_k);  kept = (keep > theta ? min(m, b) : max(m, b)) clamped to [1, #live]
+//   b    = ceil(keep * K_k) (a product within 1e-6 K_k of an integer counts as that integer);
+//          kept = (keep > theta ? min(m, b) : max(m, b)) clamped to [1, #live]
 #include "common.h"
 
 #define MASK_THREADS 256
@@ -204,8 +205,11 @@ block_mask_kernel(const double* __restrict__ abar, const int32_t* __restrict__ c
                 }
             }
         }
+        // keep arrives as a float32: a decimal ratio whose product with K_k is an integer (0.3 x 20)
+        // sits a hair above it, so a product within 1e-6 K_k of an integer is that integer
         const double kp = (double)keep[b];
-        const int budget = (int)ceil(kp * (double)kk);
+        const double prod = kp * (double)kk, nearest = rint(prod);
+        const int budget = fabs(prod - nearest) <= 1e-6 * (double)kk ? (int)nearest : (int)ceil(prod);
         int n_keep = kp > theta ? (m < budget ? m : budget) : (m > budget ? m : budget);
         n_keep = n_keep > n_live ? n_live : n_keep;
         n_keep = n_keep < 1 ? 1 : n_keep;

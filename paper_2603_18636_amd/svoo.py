@@ -36,6 +36,7 @@ _SIGNATURES = {
     "svoo_status_string": (ctypes.c_char_p, [ctypes.c_int]),
     "svoo_version": (_i32, []),
     "svoo_workspace_bytes": (_sz, [_SP]),
+    "svoo_permute_workspace_bytes": (_sz, [_SP, _i32]),
     "svoo_cocluster": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                       _vp, _sz, _vp]),
     "svoo_cocluster_sorted": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -51,6 +52,7 @@ _SIGNATURES = {
     "svoo_block_sparse_attn_tokens": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp,
                                                      _sz, _vp]),
     "svoo_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "svoo_row_recall": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp]),
     "svoo_attention_density": (ctypes.c_int, [_SP, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp]),
     "svoo_microbench_mfma_bf16": (ctypes.c_int, [_i32, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "svoo_microbench_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
@@ -236,7 +238,7 @@ def permute(labels, n_clusters: int, tensors: Sequence[torch.Tensor], ws=None, o
     dst = (ctypes.c_void_p * max(nt, 1))(*[t.data_ptr() for t in outs])
     if ws is None:
         ws = workspace(shape, dev)
-        need = bh * ((n + 511) // 512) * n_clusters * 4 + 256  # sort scratch when n_clusters > n
+        need = int(_lib().svoo_permute_workspace_bytes(ctypes.byref(shape), n_clusters))   # more bins than tokens
         if ws.numel() < need:
             buf = torch.empty(need + 256, dtype=torch.uint8, device=dev)
             off = (-buf.data_ptr()) % 256
@@ -569,7 +571,7 @@ class Layer:
     def row_recall(self, q, k, v, scale=None):
         """Diagnostic, not a step of the path: per token, the dense softmax mass that falls on the keys
         of its kept blocks, = exp(LSE over kept keys - LSE over all keys), from the two attention
-        kernels' log-sum-exp outputs for the partition, permutation and block lists this object
+        kernels' log-sum-exp outputs (svoo_row_recall) for the partition, permutation and block lists this object
         holds.  [bh, n] float32 in token order; its mean is the attention recall of the paper's
         clustering comparison.  Runs both attentions (overwrites ``out`` and ``o_sorted``)."""
         scale = 1.0 / math.sqrt(self.d) if scale is None else scale
@@ -578,7 +580,7 @@ class Layer:
         lse_d = torch.empty((bh, n), dtype=torch.float32, device=self.dev)
         self.step_attn(scale, lse=lse_s)
         self.dense(q, k, v, scale, lse=lse_d)
-        rec_sorted = torch.exp(lse_s - torch.gather(lse_d, 1, self.perm_q.long()))
-        rec = torch.empty_like(rec_sorted)
-        rec.scatter_(1, self.perm_q.long(), rec_sorted)
+        rec = torch.empty((bh, n), dtype=torch.float32, device=self.dev)
+        _run(_lib().svoo_row_recall(ctypes.byref(self.shape), _ptr(lse_s), _ptr(lse_d), _ptr(self.perm_q), _ptr(rec),
+                                    _stream()), "svoo_row_recall")
         return rec

@@ -97,6 +97,9 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
                                              4096, null) == INVALID            # no permutation
     assert lib.svoo_block_sparse_attn_tokens(sp, fake, fake, fake, fake, fake, fake, fake, fake, 0.125, fake, null, fake,
                                              8, null) == TOO_SMALL
+    assert lib.svoo_row_recall(sp, fake, fake, null, fake, null) == INVALID
+    assert svoo._lib().svoo_permute_workspace_bytes(sp, 0) == 0
+    assert svoo._lib().svoo_permute_workspace_bytes(sp, 1024) == 2 * 1024 * 4          # 2 chunks of 512 tokens x 1024 bins
     arr = (ctypes.c_void_p * 1)(0x1000)
     arr2 = (ctypes.c_void_p * 1)(0x2000)
     assert lib.svoo_permute(sp, fake, 0, 1, arr, arr2, fake, fake, fake, ws_bytes, null) == INVALID      # 0 clusters

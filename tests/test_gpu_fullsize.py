@@ -17,6 +17,7 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 CFG = synth.CONFIGS[2]
+ROWS_PER_HEAD = H.ROWS_PER_HEAD
 
 
 @pytest.fixture(scope="module")
@@ -37,45 +38,30 @@ def full_layer():
     return data, dev, keep, layer, got
 
 
-def stratified_rows(labels_q, counts_q, n_rows, rng):
-    """Sample rows covering the smallest and the largest query clusters and every cluster once."""
-    rows = []
-    live = np.nonzero(counts_q > 0)[0]
-    order = live[np.argsort(counts_q[live])]
-    for r in list(order[:4]) + list(order[-4:]):
-        members = np.nonzero(labels_q == r)[0]
-        rows.extend(members[[0, len(members) // 2, len(members) - 1]])
-    for r in live:
-        members = np.nonzero(labels_q == r)[0]
-        rows.append(members[rng.integers(0, len(members))])
-    rows.extend(rng.integers(0, labels_q.shape[0], max(0, n_rows - len(rows))))
-    return np.unique(np.array(rows, dtype=np.int64))
-
-
 def test_fullsize_head0_end_to_end(full_layer):
+    """Head 0 through the oracle end to end: labels of every half-step (a difference must be a proven
+    near-tie, after which the oracle follows the GPU), centroids, mask, >= 4096 stratified attention rows."""
     data, dev, keep, layer, got = full_layer
     b = 0
     scale = H.scale_of(CFG.d)
     q, k, v = data["q"][b], data["k"][b], data["v"][b]
-    ref = so.cocluster(q, k, data["init_q_idx"][b], data["init_k_idx"][b], CFG.iters)
-    last_k = [t for t in ref["trace"] if t["side"] == "k"][-1]
-    last_q = [t for t in ref["trace"] if t["side"] == "q"][-1]
-    near = H.compare_labels(got["labels_k"][b], ref["labels_k"], last_k["best"], last_k["second"])
-    near += H.compare_labels(got["labels_q"][b], ref["labels_q"], last_q["best"], last_q["second"])
-    print(f"near-tie label differences on head 0: {near}")
-    if near == 0:
-        np.testing.assert_array_equal(got["cq"][b], ref["cq"].astype(np.float32))
-        np.testing.assert_array_equal(got["ck"][b], ref["ck"].astype(np.float32))
-        mask = so.block_mask(ref["cq"].astype(np.float32), ref["ck"].astype(np.float32), ref["counts_q"],
-                             ref["counts_k"], np.float32(keep), 1.0, 0.0, scale)
-        margins = so.selection_margins(ref["cq"].astype(np.float32), ref["ck"].astype(np.float32), ref["counts_q"],
-                                       ref["counts_k"], np.float32(keep), 1.0, 0.0, scale)
-        ok_rows = margins >= H.NEAR_TIE
-        assert (got["bitmap"][b].astype(bool)[ok_rows] == mask[ok_rows]).all()
-        rows = stratified_rows(ref["labels_q"], ref["counts_q"], 1024, np.random.default_rng(0))
-        rows = rows[ok_rows[ref["labels_q"][rows]]]
-        out_ref = so.sparse_attention(q, k, v, ref["labels_q"], ref["labels_k"], mask, scale, rows=rows)
-        H.assert_attn_close(got["out"][b][rows], out_ref, "bf16", "full-size head 0")
+    one = {name: dev[name][b:b + 1] for name in ("q", "k", "init_q_idx", "init_k_idx")}
+    steps, _ = H.gpu_cocluster_steps(one["q"], one["k"], one["init_q_idx"], one["init_k_idx"], CFG.iters)
+    assert (steps[(CFG.iters - 1, "q")][0] == got["labels_q"][b]).all()     # heads are independent problems
+    assert (steps[(CFG.iters - 1, "k")][0] == got["labels_k"][b]).all()
+    ref = H.resync_cocluster(q, k, data["init_q_idx"][b], data["init_k_idx"][b], CFG.iters, H.slice_steps(steps, 0),
+                             what="configs[2] head 0")
+    assert (got["labels_q"][b] == ref["labels_q"]).all() and (got["labels_k"][b] == ref["labels_k"]).all()
+    np.testing.assert_array_equal(got["cq"][b], ref["cq"].astype(np.float32))
+    np.testing.assert_array_equal(got["ck"][b], ref["ck"].astype(np.float32))
+    cq32, ck32 = ref["cq"].astype(np.float32), ref["ck"].astype(np.float32)
+    mask = so.block_mask(cq32, ck32, ref["counts_q"], ref["counts_k"], np.float32(keep), 1.0, 0.0, scale)
+    margins = so.selection_margins(cq32, ck32, ref["counts_q"], ref["counts_k"], np.float32(keep), 1.0, 0.0, scale)
+    H.compare_mask(got["bitmap"][b], mask, margins, "configs[2] head 0")
+    rows = H.stratified_rows(ref["labels_q"], ref["counts_q"], ROWS_PER_HEAD, np.random.default_rng(0))
+    assert rows.size >= ROWS_PER_HEAD
+    out_ref = so.sparse_attention(q, k, v, ref["labels_q"], ref["labels_k"], mask, scale, rows=rows)
+    H.assert_attn_close(got["out"][b][rows], out_ref, "bf16", "full-size head 0")
 
 
 def test_fullsize_every_head_stepwise(full_layer):
@@ -102,12 +88,12 @@ def test_fullsize_every_head_stepwise(full_layer):
                              0.0, scale)
         margins = so.selection_margins(got["cq"][b], got["ck"][b], got["counts_q"][b], got["counts_k"][b],
                                        np.float32(keep), 1.0, 0.0, scale)
-        ok_rows = margins >= H.NEAR_TIE
         gpu_mask = got["bitmap"][b].astype(bool)
-        assert (gpu_mask[ok_rows] == mask[ok_rows]).all()
+        H.compare_mask(gpu_mask, mask, margins, f"configs[2] head {b}")
         assert (got["block_count"][b] == gpu_mask.sum(1)).all()
         # sampled attention rows with the GPU's labels and the GPU's mask
-        rows = stratified_rows(lq, got["counts_q"][b], 400, rng)
+        rows = H.stratified_rows(lq, got["counts_q"][b], ROWS_PER_HEAD, rng)
+        assert rows.size >= ROWS_PER_HEAD
         out_ref = so.sparse_attention(data["q"][b], data["k"][b], data["v"][b], lq, lk, gpu_mask, scale, rows=rows)
         e = H.assert_attn_close(got["out"][b][rows], out_ref, "bf16", f"full-size head {b}")
         worst = (max(worst[0], e[0]), max(worst[1], e[1]))

@@ -132,10 +132,16 @@ def test_key_partition_follows_the_query_anchors(dtype, d):
 
 # ------------------------------------------------------------------------------------------ cocluster
 def run_cocluster_case(h, iters, dtype, want_objective=False):
+    """svoo_cocluster next to the oracle, half-step by half-step (the oracle follows the GPU through
+    proven near-ties, so everything after the labels is always compared)."""
     q, k = h["q"], h["k"]
-    out = svoo.cocluster(H.to_dev(q[None], dtype), H.to_dev(k[None], dtype), H.to_dev(h["init_q_idx"][None]),
-                         H.to_dev(h["init_k_idx"][None]), iters, want_objective=want_objective)
-    ref = so.cocluster(q, k, h["init_q_idx"], h["init_k_idx"], iters)
+    qd, kd = H.to_dev(q[None], dtype), H.to_dev(k[None], dtype)
+    iq, ik = H.to_dev(h["init_q_idx"][None]), H.to_dev(h["init_k_idx"][None])
+    steps, _ = H.gpu_cocluster_steps(qd, kd, iq, ik, iters)
+    out = svoo.cocluster(qd, kd, iq, ik, iters, want_objective=want_objective)
+    assert (H.to_np(out["labels_k"]) == steps[(iters - 1, "k")]).all()      # the objective pass changes nothing
+    assert (H.to_np(out["labels_q"]) == steps[(iters - 1, "q")]).all()
+    ref = H.resync_cocluster(q, k, h["init_q_idx"], h["init_k_idx"], iters, H.slice_steps(steps, 0))
     return out, ref
 
 
@@ -143,24 +149,23 @@ def run_cocluster_case(h, iters, dtype, want_objective=False):
 def test_cocluster_matches_oracle(dtype, d, iters):
     h = small_cfg1_head(d=d, dtype=dtype)
     out, ref = run_cocluster_case(h, iters, dtype, want_objective=True)
-    last_k = [t for t in ref["trace"] if t["side"] == "k"][-1]
-    last_q = [t for t in ref["trace"] if t["side"] == "q"][-1]
-    near = H.compare_labels(H.to_np(out["labels_k"])[0], ref["labels_k"], last_k["best"], last_k["second"])
-    near += H.compare_labels(H.to_np(out["labels_q"])[0], ref["labels_q"], last_q["best"], last_q["second"])
-    if near == 0:
-        assert (H.to_np(out["counts_q"])[0] == ref["counts_q"]).all()
-        assert (H.to_np(out["counts_k"])[0] == ref["counts_k"]).all()
-        np.testing.assert_array_equal(H.to_np(out["cq"])[0], ref["cq"].astype(np.float32))
-        np.testing.assert_array_equal(H.to_np(out["ck"])[0], ref["ck"].astype(np.float32))
-        obj = H.to_np(out["objective"])[0]
-        j_ref = np.array([t["J"] for t in ref["trace"]]).reshape(iters, 2)
-        np.testing.assert_allclose(obj, j_ref, rtol=1e-9)
+    assert (H.to_np(out["labels_k"])[0] == ref["labels_k"]).all()
+    assert (H.to_np(out["labels_q"])[0] == ref["labels_q"]).all()
+    assert (H.to_np(out["counts_q"])[0] == ref["counts_q"]).all()
+    assert (H.to_np(out["counts_k"])[0] == ref["counts_k"]).all()
+    np.testing.assert_array_equal(H.to_np(out["cq"])[0], ref["cq"].astype(np.float32))
+    np.testing.assert_array_equal(H.to_np(out["ck"])[0], ref["ck"].astype(np.float32))
+    if ref["near"] == 0:     # the objective is a sum over labels: the oracle's own sum only when no label moved
+        plain = so.cocluster(h["q"], h["k"], h["init_q_idx"], h["init_k_idx"], iters)
+        j_ref = np.array([t["J"] for t in plain["trace"]]).reshape(iters, 2)
+        np.testing.assert_allclose(H.to_np(out["objective"])[0], j_ref, rtol=1e-9)
 
 
 def test_cocluster_config0_full():
     cfg = synth.CONFIGS[0]
     h = synth.make_head(cfg, 0, 0)
     out, ref = run_cocluster_case(h, cfg.iters, "f32")
+    assert ref["near"] == 0
     assert (H.to_np(out["labels_q"])[0] == ref["labels_q"]).all()
     assert (H.to_np(out["labels_k"])[0] == ref["labels_k"]).all()
     np.testing.assert_array_equal(H.to_np(out["cq"])[0], ref["cq"].astype(np.float32))
@@ -214,13 +219,32 @@ def test_block_mask_bit_exact(mode, kq, kk, d):
     for b in range(bh):
         ref = so.block_mask(cq[b], ck[b], nq[b], nk[b], keep[b], tau32, theta32, scale)
         margins = so.selection_margins(cq[b], ck[b], nq[b], nk[b], keep[b], tau32, theta32, scale)
+        equal, flipped = H.compare_mask(bitmap[b], ref, margins, f"{mode} kq={kq} kk={kk} slice {b}")
+        assert equal == kq and flipped == 0
         for r in range(kq):
-            if margins[r] < H.NEAR_TIE:
-                continue
-            assert (bitmap[b, r].astype(bool) == ref[r]).all(), (b, r)
             assert cnt[b, r] == ref[r].sum()
             assert (lst[b, r, :cnt[b, r]] == np.nonzero(ref[r])[0]).all()
             assert (lst[b, r, cnt[b, r]:] == -1).all()
+
+
+@pytest.mark.parametrize("keep,kk,want", [(0.3, 20, 6), (0.2, 1000, 200), (0.1, 1000, 100), (0.7, 10, 7), (0.26, 4, 2)])
+def test_block_mask_decimal_keep_is_the_real_number(keep, kk, want):
+    """keep crosses the boundary as a float32 (0.3f * 20 = 6.0000002): the budget is still ceil of the
+    real-number product, on the GPU as in the oracle handed the unrounded decimal."""
+    rng = np.random.default_rng(kk)
+    kq, d = 3, 64
+    cq = rng.standard_normal((1, kq, d)).astype(np.float32)
+    ck = rng.standard_normal((1, kk, d)).astype(np.float32)
+    nq = np.full((1, kq), 5, dtype=np.int32)
+    nk = np.full((1, kk), 7, dtype=np.int32)
+    scale = H.scale_of(d)
+    cnt, lst, bitmap = svoo.block_mask(H.to_dev(cq), H.to_dev(ck), H.to_dev(nq), H.to_dev(nk),
+                                       H.to_dev(np.array([keep], dtype=np.float32)), 1.0, 0.0, scale)
+    assert (H.to_np(cnt) == want).all()
+    ref = so.block_mask(cq[0], ck[0], nq[0], nk[0], keep, 1.0, 0.0, scale)           # keep as the Python decimal
+    assert (ref.sum(1) == want).all()
+    margins = so.selection_margins(cq[0], ck[0], nq[0], nk[0], keep, 1.0, 0.0, scale)
+    H.compare_mask(H.to_np(bitmap)[0], ref, margins, "decimal keep")
 
 
 # ------------------------------------------------------------------------------------------ attention

@@ -11,8 +11,6 @@ from tests import helpers as H
 
 pytestmark = pytest.mark.gpu
 
-DIVERGED = []
-
 
 def random_case(seed):
     rng = np.random.default_rng(1000 + seed)
@@ -65,7 +63,10 @@ def test_sparse_attention_random_layout(seed):
 
 @pytest.mark.parametrize("seed", range(24, 40))
 def test_layer_random_small_shapes(seed):
-    """Whole layer (co-clustering, mask, attention) on random small shapes against the oracle."""
+    """Whole layer (co-clustering, mask, attention) on random small shapes against the oracle.  Labels
+    are compared half-step by half-step; a difference must be a proven near-tie of that half-step,
+    and the oracle then continues from the GPU's labels, so centroids, mask and attention are
+    checked on every slice."""
     rng, d, dtype, n, kq, kk, bh, q, k, v = random_case(seed)
     iters = int(rng.integers(1, 4))
     keep = float(np.float32(rng.uniform(0.1, 1.0)))
@@ -73,33 +74,29 @@ def test_layer_random_small_shapes(seed):
     init_q = np.stack([synth.sample_distinct(rng, n, kq) for _ in range(bh)])
     init_k = np.stack([synth.sample_distinct(rng, n, kk) for _ in range(bh)])
     layer = svoo.Layer(bh, n, d, H.torch_dtype(dtype), kq, kk, H.DEV)
-    out = layer.run(H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype), H.to_dev(init_q), H.to_dev(init_k),
-                    iters, H.to_dev(np.full(bh, keep, dtype=np.float32)), tau, theta)
+    qd, kd, vd = H.to_dev(q, dtype), H.to_dev(k, dtype), H.to_dev(v, dtype)
+    iqd, ikd = H.to_dev(init_q), H.to_dev(init_k)
+    out = layer.run(qd, kd, vd, iqd, ikd, iters, H.to_dev(np.full(bh, keep, dtype=np.float32)), tau, theta)
     torch.cuda.synchronize()
     out = H.to_np(out)
+    steps, _ = H.gpu_cocluster_steps(qd, kd, iqd, ikd, iters)
+    assert (steps[(iters - 1, "q")] == H.to_np(layer.labels_q)).all()
+    assert (steps[(iters - 1, "k")] == H.to_np(layer.labels_k)).all()
     scale = H.scale_of(d)
     for b in range(bh):
-        cc = so.cocluster(q[b], k[b], init_q[b], init_k[b], iters)
-        same = (H.to_np(layer.labels_q)[b] == cc["labels_q"]).all() and (H.to_np(layer.labels_k)[b] == cc["labels_k"]).all()
-        if not same:
-            # a label may only differ at a near-tie of the assignment; then the rest of the run legitimately
-            # diverges (the step-wise tests cover that case) -- report it, it must stay rare
-            print(f"seed {seed} slice {b}: labels differ from the oracle's, slice skipped")
-            DIVERGED.append((seed, b))
-            continue
+        what = f"seed {seed} slice {b} (n={n}, kq={kq}, kk={kk}, d={d}, {dtype})"
+        cc = H.resync_cocluster(q[b], k[b], init_q[b], init_k[b], iters, H.slice_steps(steps, b), what=what)
         lq, lk = cc["labels_q"], cc["labels_k"]
+        assert (H.to_np(layer.labels_q)[b] == lq).all() and (H.to_np(layer.labels_k)[b] == lk).all()
+        assert (H.to_np(layer.counts_q)[b] == cc["counts_q"]).all() and (H.to_np(layer.counts_k)[b] == cc["counts_k"]).all()
         cq32, ck32 = H.to_np(layer.cq)[b], H.to_np(layer.ck)[b]
-        np.testing.assert_allclose(cq32, cc["cq"], rtol=2e-6, atol=1e-6)
+        np.testing.assert_array_equal(cq32, cc["cq"].astype(np.float32))
+        np.testing.assert_array_equal(ck32, cc["ck"].astype(np.float32))
         mask = so.block_mask(cq32.astype(np.float64), ck32.astype(np.float64), cc["counts_q"], cc["counts_k"],
                              np.float32(keep), tau, theta, scale)
         margins = so.selection_margins(cq32.astype(np.float64), ck32.astype(np.float64), cc["counts_q"], cc["counts_k"],
                                        np.float32(keep), tau, theta, scale)
         gpu_mask = H.to_np(layer.bitmap)[b].astype(bool)
-        ok = margins >= H.NEAR_TIE
-        assert (gpu_mask[ok] == mask[ok]).all()
+        H.compare_mask(gpu_mask, mask, margins, what)
         ref = so.sparse_attention(q[b], k[b], v[b], lq, lk, gpu_mask, scale)
-        H.assert_attn_close(out[b], ref, dtype, f"seed {seed} slice {b} (n={n}, kq={kq}, kk={kk}, d={d}, {dtype})")
-
-
-def test_random_layers_rarely_diverge():
-    assert len(DIVERGED) <= 1, DIVERGED
+        H.assert_attn_close(out[b], ref, dtype, what)

@@ -2,6 +2,7 @@
 forms, invariants and brute force on tiny inputs.  A plausible mistake in the oracle (dropped
 term, wrong sign or index, transposed operand, wrong centroid version) fails at least one."""
 import math
+import warnings
 
 import os
 
@@ -311,6 +312,100 @@ def test_selection_rule_hand_cases():
     assert so.select_blocks(w3, live, keep=1.0, tau=0.75, theta=0.1).tolist() == [False, True, False, True]
 
 
+def test_budget_counts_decimal_keep_ratios_as_the_real_number():
+    """keep reaches the library as a float32, so 0.3 * 20 arrives as 6.0000002: the budget must still
+    be 6 blocks (and 200 of 1000 at 0.2, 100 of 1000 at 0.1), while a product that is not an integer
+    keeps its ceiling."""
+    for keep, kk, want in ((0.3, 20, 6), (0.2, 1000, 200), (0.1, 1000, 100), (0.7, 10, 7), (0.26, 4, 2),
+                           (0.25, 4, 1), (0.2, 256, 52), (0.15, 512, 77), (1.0, 1024, 1024), (0.0, 16, 0)):
+        assert so.budget_blocks(np.float32(keep), kk) == want, (keep, kk)
+        assert so.budget_blocks(keep, kk) == want, (keep, kk)
+    w = np.full(20, 0.05)
+    assert so.select_blocks(w, np.ones(20, dtype=bool), np.float32(0.3), 1.0, 0.0).sum() == 6
+
+
+# weights that are exact in floating point: all-zero centroids give logit 0 everywhere, so the
+# size-weighted softmax is counts / sum(counts)
+def _weights_from_counts(counts_k, kq=1):
+    counts_k = np.asarray(counts_k)
+    cq, ck = np.zeros((kq, 2)), np.zeros((counts_k.shape[0], 2))
+    return cq, ck, np.ones(kq, dtype=np.int64), counts_k
+
+
+def test_selection_margins_hand_rows():
+    """Hand-computed margins: (a) relative weight gap between the last kept and the first dropped
+    block, (b) relative distance of a cumulative weight from tau; the smaller of the two."""
+    cq, ck, nq, nk = _weights_from_counts([4, 2, 1, 1])           # w = 0.5 0.25 0.125 0.125, cumsum 0.5 0.75 0.875 1
+    m = lambda keep, tau, theta: so.selection_margins(cq, ck, nq, nk, keep, tau, theta, 1.0)[0]
+    assert m(1.0, 0.75, 0.1) == 0.0                               # the cumulative weight hits tau exactly
+    assert m(0.5, 1.0, 0.0) == 0.5                                # budget 2: gap (0.25 - 0.125) / 0.25, no tau term
+    assert m(0.75, 1.0, 0.0) == 0.0                               # budget 3: the cut runs through two equal weights
+    assert m(1.0, 1.0, 0.0) == np.inf                             # everything kept, nothing can flip
+    assert m(1.0, 0.8, 0.1) == 0.0                                # 3 kept by recall, cut between equal weights
+    cq, ck, nq, nk = _weights_from_counts([4, 3, 2, 1])           # w = 0.4 0.3 0.2 0.1, cumsum 0.4 0.7 0.9 1.0
+    got = so.selection_margins(cq, ck, nq, nk, 1.0, 0.65, 0.1, 1.0)[0]
+    assert abs(got - 0.05 / 0.65) < 1e-12                         # 2 kept; gap 1/3, tau distance 0.05 / 0.65
+    got = so.selection_margins(cq, ck, nq, nk, 1.0, 0.5, 0.1, 1.0)[0]
+    assert abs(got - 0.2) < 1e-12                                 # 2 kept; |0.4 - 0.5| / 0.5 = 0.2 < gap 1/3
+    got = so.selection_margins(cq, ck, nq, nk, 0.25, 0.95, 0.1, 1.0)[0]
+    assert abs(got - 0.05 / 0.95) < 1e-12                         # budget 1 wins; tau still 0.05 from a cumsum
+    got = so.selection_margins(cq, ck, nq, nk, 0.25, 1.0, 0.0, 1.0)[0]
+    assert abs(got - 0.25) < 1e-12                                # (0.4 - 0.3) / 0.4
+    # empty query block and a slice without keys: nothing to flip
+    cq, ck, nq, nk = _weights_from_counts([4, 3, 2, 1], kq=2)
+    nq = np.array([3, 0])
+    got = so.selection_margins(cq, ck, nq, nk, 0.5, 1.0, 0.0, 1.0)
+    assert abs(got[0] - 1.0 / 3.0) < 1e-12 and got[1] == np.inf
+    assert so.selection_margins(cq, ck, nq, np.zeros(4, dtype=np.int64), 0.5, 1.0, 0.0, 1.0).tolist() == [np.inf, np.inf]
+
+
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("mode", ["budget", "paper", "top_p"])
+def test_selection_margin_bounds_the_perturbation_that_flips_the_mask(seed, mode):
+    """A change of every logit by at most delta multiplies every weight, and every cumulative
+    weight, by a factor in [exp(-2 delta), exp(2 delta)].  So (i) while exp(4 delta) - 1 stays below
+    the margin of every row the mask cannot change, and (ii) raising the logit of the first dropped
+    block of a row by a little more than -log(1 - gap) must change that row when the gap is what
+    the margin reports."""
+    rng = np.random.default_rng(500 + seed)
+    kq, kk, d = 6, 24, 8
+    cq, ck = rng.standard_normal((kq, d)) * 1.5, rng.standard_normal((kk, d)) * 1.5
+    nq, nk = rng.integers(1, 40, kq), rng.integers(0, 40, kk)
+    nk[3] = 0
+    scale = 1.0 / math.sqrt(d)
+    keep, tau, theta = {"budget": (0.3, 1.0, 0.0), "paper": (0.3, 0.9, 0.1), "top_p": (1.0, 0.8, 0.1)}[mode]
+    base = so.block_mask(cq, ck, nq, nk, keep, tau, theta, scale)
+    margins = so.selection_margins(cq, ck, nq, nk, keep, tau, theta, scale)
+    assert np.isfinite(margins).all() and (margins > 0).all()
+    # (i) perturbations of the key centroids that move every logit by less than delta
+    delta = math.log1p(margins.min()) / 4.0 * 0.99
+    qn = np.linalg.norm(cq, axis=1).max()
+    for trial in range(20):
+        step = rng.standard_normal(ck.shape)
+        step *= (delta / (scale * qn)) / np.linalg.norm(step, axis=1, keepdims=True)
+        assert (so.block_mask(cq, ck + step, nq, nk, keep, tau, theta, scale) == base).all()
+    # (ii) the gap part is tight: lift the first dropped block of a row just past the last kept one
+    w = so.block_weights(cq, ck, nk, scale)
+    live = np.nonzero(nk > 0)[0]
+    for r in range(kq):
+        order = live[np.argsort(-w[r, live], kind="stable")]
+        n_keep = int(base[r].sum())
+        if n_keep == order.size:
+            continue
+        last, first_dropped = order[n_keep - 1], order[n_keep]
+        gap = (w[r, last] - w[r, first_dropped]) / w[r, last]
+        assert margins[r] <= gap + 1e-15
+        if mode != "budget":
+            continue          # with a recall threshold the number kept may move too; the order flip is pinned in budget mode
+        lift = -math.log1p(-gap) * (1.0 + 1e-6) + 1e-12
+        ck2 = ck.copy()
+        ck2[first_dropped] += lift * cq[r] / (scale * cq[r] @ cq[r])       # raises logit (r, first_dropped) by `lift`
+        assert so.block_mask(cq, ck2, nq, nk, keep, tau, theta, scale)[r, first_dropped]
+        ck3 = ck.copy()
+        ck3[first_dropped] += 0.5 * lift * cq[r] / (scale * cq[r] @ cq[r])  # half the way: below the gap, no flip
+        assert (so.block_mask(cq, ck3, nq, nk, keep, tau, theta, scale)[r] == base[r]).all()
+
+
 def test_block_mask_skips_empty_query_clusters():
     cq = np.random.default_rng(0).standard_normal((3, 4))
     ck = np.random.default_rng(1).standard_normal((2, 4))
@@ -537,3 +632,61 @@ def test_key_partition_depends_on_the_query_anchors():
             assert got == parts[which], (which, first_two, got)
     a = so.kmeans(keys, np.array([0, 2], dtype=np.int32), 3)["labels"]
     assert len(set(a.tolist())) <= 2      # and it is the same whatever the queries are: they are not an input
+
+
+# ---------------------------------------------------------------------------- parity-harness logic
+def test_resync_follows_only_proven_near_ties():
+    """The step-wise comparison used by the GPU parity tests, exercised on the CPU with planted
+    labels: the oracle's own labels pass with zero differences; a flipped label at an exact tie is
+    accepted, counted, and the later half-steps continue from it; a flipped label that is no tie is
+    an error."""
+    h = tiny_head()
+    q, k = h["q"].copy(), h["k"].copy()
+    k[7] = k[3]                                     # two identical keys
+    init_q, init_k = h["init_q_idx"], np.array([3, 7, 11, 20, 40], dtype=np.int32)   # anchors 0 and 1 coincide
+    iters = 2
+    ref = so.cocluster(q, k, init_q, init_k, iters)
+    steps = {(t["iter"], t["side"]): t["labels"].copy() for t in ref["trace"]}
+    with warnings.catch_warnings():
+        warnings.simplefilter("error")
+        same = H.resync_cocluster(q, k, init_q, init_k, iters, steps)
+    assert same["near"] == 0 and (same["labels_q"] == ref["labels_q"]).all()
+    np.testing.assert_array_equal(same["cq"], ref["cq"])
+    # every key whose two best anchors are the coinciding ones sits at an exact tie in the first Step A
+    first = ref["trace"][0]
+    tied = np.nonzero((first["labels"] == 0) & (first["second"] == first["best"]))[0]
+    assert tied.size > 0
+    flipped = dict(steps)
+    flipped[(0, "k")] = steps[(0, "k")].copy()
+    flipped[(0, "k")][tied[0]] = 1                  # the other member of the tie
+    # later half-steps of a run that took the other branch: recompute them the slow way
+    ck1, _ = so.update_centroids(k.astype(np.float64), flipped[(0, "k")], k[init_k].astype(np.float64))
+    lq0, cq1, *_ = so.half_step(q.astype(np.float64), q[init_q].astype(np.float64), ck1)
+    flipped[(0, "q")] = lq0
+    rest = so.cocluster(q, k, None, None, 1, init_cq=cq1, init_ck=ck1)
+    flipped[(1, "k")], flipped[(1, "q")] = rest["labels_k"], rest["labels_q"]
+    with pytest.warns(UserWarning, match="near-ties"):
+        got = H.resync_cocluster(q, k, init_q, init_k, iters, flipped)
+    assert got["near"] == 1 and got["near_steps"][0] == 1 and sum(got["near_steps"][1:]) == 0
+    np.testing.assert_array_equal(got["cq"], rest["cq"])
+    # a wrong label that is no near-tie must fail
+    wrong = dict(steps)
+    wrong[(1, "q")] = steps[(1, "q")].copy()
+    clear = np.argmax(ref["trace"][3]["second"] - ref["trace"][3]["best"])
+    wrong[(1, "q")][clear] = (wrong[(1, "q")][clear] + 1) % 4
+    with pytest.raises(AssertionError, match="beyond near-ties"):
+        H.resync_cocluster(q, k, init_q, init_k, iters, wrong)
+
+
+def test_compare_mask_compares_every_row_and_bounds_near_tie_differences():
+    ref = np.array([[1, 0, 1], [0, 1, 1]], dtype=bool)
+    assert H.compare_mask(ref.copy(), ref, np.array([0.5, np.inf])) == (2, 0)
+    assert H.compare_mask(ref.copy(), ref, np.array([0.5, 1e-9])) == (2, 0)       # a near-tie row that agrees is compared
+    other = ref.copy()
+    other[1, 0] = True
+    with pytest.raises(AssertionError, match="near-ties"):
+        H.compare_mask(other, ref, np.array([0.5, 1e-9]))                        # differs at a near-tie: over the bound 0
+    with pytest.warns(UserWarning, match="near-ties"):
+        assert H.compare_mask(other, ref, np.array([0.5, 1e-9]), max_near_tie_rows=1) == (1, 1)
+    with pytest.raises(AssertionError, match="differ from the oracle"):
+        H.compare_mask(other, ref, np.array([0.5, 0.5]), max_near_tie_rows=5)    # differs with a clear margin: always wrong

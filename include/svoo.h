@@ -53,7 +53,8 @@ typedef enum {
     SVOO_ERR_INVALID_ARG = 1,         /* null required pointer, size out of range, bad alignment */
     SVOO_ERR_UNSUPPORTED = 2,         /* d or dtype the kernels do not cover */
     SVOO_ERR_WORKSPACE_TOO_SMALL = 3, /* ws_bytes below what this call needs */
-    SVOO_ERR_HIP = 4                  /* a HIP launch reported an error */
+    SVOO_ERR_HIP = 4,                 /* a HIP launch reported an error */
+    SVOO_ERR_STATIC_LIMIT = 5         /* shape beyond the fixed scratch of svoo_block_sparse_attn_static */
 } svoo_status;
 
 typedef enum { SVOO_BF16 = 0, SVOO_F32 = 1 } svoo_dtype;
@@ -232,6 +233,23 @@ int svoo_block_sparse_attn_tokens(const svoo_shape* shape, const void* q, const 
                                   const int32_t* k_offsets, const int32_t* block_count,
                                   const int32_t* block_list, float scale, void* out, float* lse,
                                   void* ws, size_t ws_bytes, void* hip_stream);
+
+/*
+ * svoo_block_sparse_attn for callers that cannot allocate device memory or carry a workspace: code
+ * recorded into a HIP graph, tight serving loops between two re-clusterings, harnesses that forbid
+ * hipMalloc.  Same arguments without (ws, ws_bytes), same kernels, same results bit for bit.  The one
+ * piece of scratch the attention needs (the query-tile schedule, bh * (kq + 1) int32) lives in a
+ * 1 MiB device array inside the library, which every GPU the library runs on holds until the process
+ * ends; the call allocates nothing and frees nothing.  Limit: bh * (kq + 1) <= 262,144, otherwise
+ * SVOO_ERR_STATIC_LIMIT and nothing is launched (split the slices over several calls).  All calls on
+ * one GPU share that array: two calls that overlap in time on one GPU (different streams, or
+ * different host threads) race on it and must be ordered by the caller; calls on one stream are safe.
+ * Nothing in the array has to survive between calls and nothing needs clearing.
+ */
+int svoo_block_sparse_attn_static(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
+                                  const void* v_sorted, const int32_t* q_offsets, const int32_t* k_offsets,
+                                  const int32_t* block_count, const int32_t* block_list, float scale,
+                                  void* out_sorted, float* lse, void* hip_stream);
 
 /* Dense attention out = softmax(scale * Q K^T) V in token order; kq, kk of the shape are ignored. */
 int svoo_attn(const svoo_shape* shape, const void* q, const void* k, const void* v, float scale,

@@ -13,6 +13,7 @@ extern "C" const char* svoo_status_string(int status) {
         case SVOO_ERR_UNSUPPORTED: return "unsupported head dimension or dtype";
         case SVOO_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case SVOO_ERR_HIP: return "HIP launch failed";
+        case SVOO_ERR_STATIC_LIMIT: return "shape exceeds the fixed scratch of the allocation-free entry point";
         default: return "unknown status";
     }
 }

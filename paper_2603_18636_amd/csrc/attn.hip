@@ -821,6 +821,51 @@ extern "C" int svoo_block_sparse_attn(const svoo_shape* shape, const void* q_sor
                              block_list, scale, out_sorted, lse, ws, ws_bytes, hip_stream);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate or hand over a workspace (code under HIP graph
+// capture, tight serving loops): the query-tile schedule, the only scratch the attention needs,
+// lives in a file-scope device array.  In host code the array's NAME is a stand-in, not a device
+// address: its address on the current device comes from hipGetSymbolAddress, once per device, and
+// only that pointer is ever handed to a kernel.
+// ---------------------------------------------------------------------------------------------
+#define STATIC_SCRATCH_INTS (256 * 1024)     // 1 MiB per GPU: room for bh * (kq + 1) <= 262,144 schedule entries
+static __device__ __align__(256) int32_t scratch[STATIC_SCRATCH_INTS];
+static int32_t* scratch_ptr[SVOO_MAX_DEVICES];   // device address of `scratch`, per device ordinal
+
+static int32_t* static_scratch_on_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SVOO_MAX_DEVICES) return nullptr;
+    int32_t* p = __atomic_load_n(&scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void* sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return nullptr;
+        p = (int32_t*)sym;
+        __atomic_store_n(&scratch_ptr[dev], p, __ATOMIC_RELEASE);   // two racing first calls store the same address
+    }
+    return p;
+}
+
+extern "C" int svoo_block_sparse_attn_static(const svoo_shape* shape, const void* q_sorted, const void* k_sorted,
+                                             const void* v_sorted, const int32_t* q_offsets,
+                                             const int32_t* k_offsets, const int32_t* block_count,
+                                             const int32_t* block_list, float scale, void* out_sorted, float* lse,
+                                             void* hip_stream) {
+    int st = check_shape(shape, true);
+    if (st != SVOO_OK) return st;
+    if (!q_sorted || !k_sorted || !v_sorted || !q_offsets || !k_offsets || !block_count || !block_list || !out_sorted)
+        return SVOO_ERR_INVALID_ARG;
+    if (!aligned16(q_sorted) || !aligned16(k_sorted) || !aligned16(v_sorted) || !aligned16(out_sorted))
+        return SVOO_ERR_INVALID_ARG;
+    if (!(scale > 0.0f) || !(scale < 1e30f) || shape->bh > 65535) return SVOO_ERR_INVALID_ARG;
+    if ((long long)shape->bh * (shape->kq + 1) > STATIC_SCRATCH_INTS) return SVOO_ERR_STATIC_LIMIT;
+    int32_t* tile_prefix = static_scratch_on_current_device();
+    if (!tile_prefix) return SVOO_ERR_HIP;
+    AttnArgs a = {q_sorted, k_sorted, v_sorted, out_sorted, lse, q_offsets, k_offsets, block_count, block_list,
+                  nullptr, nullptr, shape->n, shape->kq, shape->kk, scale};
+    // the schedule kernel rewrites every entry this shape uses, so nothing of an earlier call needs clearing
+    return launch_sparse(shape, a, tile_prefix, false, (hipStream_t)hip_stream);
+}
+
 extern "C" int svoo_block_sparse_attn_tokens(const svoo_shape* shape, const void* q, const int32_t* q_perm,
                                              const void* k_sorted, const void* v_sorted, const int32_t* q_offsets,
                                              const int32_t* k_offsets, const int32_t* block_count,

@@ -49,6 +49,7 @@ _SIGNATURES = {
     "svoo_unpermute": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp]),
     "svoo_block_mask": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "svoo_block_sparse_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "svoo_block_sparse_attn_static": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp]),
     "svoo_block_sparse_attn_tokens": (ctypes.c_int, [_SP, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp,
                                                      _sz, _vp]),
     "svoo_attn": (ctypes.c_int, [_SP, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _sz, _vp]),
@@ -321,6 +322,27 @@ def block_sparse_attn(q_sorted, k_sorted, v_sorted, q_offsets, k_offsets, block_
                                        _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream())
     _run(st, "svoo_block_sparse_attn")
     return (out, lse) if want_lse else out
+
+
+def block_sparse_attn_static(q_sorted, k_sorted, v_sorted, q_offsets, k_offsets, block_count, block_list, scale: float,
+                             out, lse=None):
+    """svoo_block_sparse_attn_static: the caller passes every buffer (also ``out`` and ``lse``); neither
+    this wrapper nor the library allocates."""
+    bh, n, d = q_sorted.shape
+    kq, kk = q_offsets.shape[1] - 1, k_offsets.shape[1] - 1
+    shape = make_shape(q_sorted, kq, kk)
+    for name, t in (("q_sorted", q_sorted), ("k_sorted", k_sorted), ("v_sorted", v_sorted), ("out", out)):
+        _check(t, q_sorted.dtype, (bh, n, d), name)
+    _check(q_offsets, torch.int32, (bh, kq + 1), "q_offsets")
+    _check(k_offsets, torch.int32, (bh, kk + 1), "k_offsets")
+    _check(block_count, torch.int32, (bh, kq), "block_count")
+    _check(block_list, torch.int32, (bh, kq, kk), "block_list")
+    _check(lse, torch.float32, (bh, n), "lse")
+    st = _lib().svoo_block_sparse_attn_static(ctypes.byref(shape), _ptr(q_sorted), _ptr(k_sorted), _ptr(v_sorted),
+                                              _ptr(q_offsets), _ptr(k_offsets), _ptr(block_count), _ptr(block_list),
+                                              scale, _ptr(out), _ptr(lse), _stream())
+    _run(st, "svoo_block_sparse_attn_static")
+    return out
 
 
 def block_sparse_attn_tokens(q, q_perm, k_sorted, v_sorted, q_offsets, k_offsets, block_count, block_list, scale: float,

@@ -97,6 +97,12 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
                                              4096, null) == INVALID            # no permutation
     assert lib.svoo_block_sparse_attn_tokens(sp, fake, fake, fake, fake, fake, fake, fake, fake, 0.125, fake, null, fake,
                                              8, null) == TOO_SMALL
+    static = lib.svoo_block_sparse_attn_static
+    assert static(sp, fake, fake, fake, fake, fake, fake, null, 0.125, fake, null, null) == INVALID
+    assert static(sp, fake, odd, fake, fake, fake, fake, fake, 0.125, fake, null, null) == INVALID
+    big = svoo.Shape(300, 2048, 64, svoo.SVOO_BF16, 1024, 16)           # 300 * 1025 schedule entries > 262,144
+    assert static(ctypes.byref(big), fake, fake, fake, fake, fake, fake, fake, 0.125, fake, null, null) == 5
+    assert "allocation-free" in svoo.status_string(5)
     assert lib.svoo_row_recall(sp, fake, fake, null, fake, null) == INVALID
     assert svoo._lib().svoo_permute_workspace_bytes(sp, 0) == 0
     assert svoo._lib().svoo_permute_workspace_bytes(sp, 1024) == 2 * 1024 * 4          # 2 chunks of 512 tokens x 1024 bins

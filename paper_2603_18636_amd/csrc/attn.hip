@@ -252,7 +252,8 @@ sparse_attn_bf16_kernel(AttnArgs a) {
     TileInfo ti;
     if (!setup_tile<NT>(a, BM, seg_start, seg_cum, scan, ti)) return;
     const int b = blockIdx.y, tid = threadIdx.x;
-    const int wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);    // uniform: keeps everything derived from it scalar
+    const int lane = tid % 64, j = lane % 32, h = lane / 32;
     const uint16_t* qg = (const uint16_t*)a.q + (size_t)b * a.n * D;
     const unsigned char* kg = (const unsigned char*)a.k + (size_t)b * a.n * ROWB;
     const unsigned char* vg = (const unsigned char*)a.v + (size_t)b * a.n * ROWB;
@@ -285,16 +286,23 @@ sparse_attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) next_rows[i] = __shfl(myrow, i * RPL + lane / CPR);
     };
+    // Tile row rho = RW wave + i RPL + lane / CPR is fetched by this lane's i-th wave-load; the three terms
+    // occupy disjoint bits, so the swizzled 16-byte chunk of load i is that of load 0 XOR a constant
+    // (K) or the same (V: its swizzle only looks at row bits below RPL).  The loads take the slice's
+    // base address as a scalar and a 32-bit byte offset per lane: one shift-add per load, no 64-bit
+    // address arithmetic in vector registers.
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+    const uint32_t kx0 = (uint32_t)(((lane % CPR) ^ ((RW * wave + lane / CPR) % CPR)) * 16);
+    const uint32_t vx0 = (uint32_t)(((lane % CPR) ^ vswz(RW * wave + lane / CPR)) * 16);
     auto issue_prepared = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int rho = RW * wave + i * RPL + lane / CPR;     // tile row
-            const int kchunk = (lane % CPR) ^ (rho % CPR);
-            const int vchunk = (lane % CPR) ^ vswz(rho);
-            const uint32_t goff = (uint32_t)next_rows[i] * ROWB;
-            const int loff = buf * TILE + (RW * wave + i * RPL) * ROWB;
-            load_global_to_lds_16(kg + goff + kchunk * 16, lds_address(k_lds) + loff);
-            load_global_to_lds_16(vg + goff + vchunk * 16, lds_address(v_lds) + loff);
+            const uint32_t row_off = (uint32_t)next_rows[i] * ROWB;      // < 2^32: n <= 2^24 rows of at most 256 bytes
+            const uint32_t koffs = row_off + (kx0 ^ (uint32_t)(((i * RPL) % CPR) * 16));
+            const uint32_t voffs = row_off + vx0;
+            const uint32_t loff = lds0 + buf * TILE + (RW * wave + i * RPL) * ROWB;
+            load_rows_to_lds_16(koffs, kg, loff);
+            load_rows_to_lds_16(voffs, vg, loff + NBUF * TILE);
         }
     };
 

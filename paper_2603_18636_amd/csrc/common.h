@@ -42,6 +42,15 @@ __device__ __forceinline__ void load_global_to_lds_16(const void* gptr, uint32_t
                  : "v"(gptr), "s"(__builtin_amdgcn_readfirstlane(lds_addr))
                  : "memory", "m0");
 }
+
+// The same with a wave-uniform 64-bit base address (kept in scalar registers) and a 32-bit byte
+// offset per lane.
+__device__ __forceinline__ void load_rows_to_lds_16(uint32_t byte_offset, const void* uniform_base, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(byte_offset), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_addr))
+                 : "memory", "m0");
+}
 #pragma clang diagnostic pop
 
 __device__ __forceinline__ uint32_t lds_address(const void* p) {

@@ -445,6 +445,24 @@ def main():
         torch.cuda.synchronize()
         measured["copy_GBps"] = round(5 * moved / (m0.elapsed_time(m1) * 1e-3) / 1e9, 1)
         measured["copy_bytes"] = moved
+        # the data movement of one attention tile step through the LDS, piece by piece and with the matrix
+        # instructions it feeds (no softmax): what an LDS-fed tile loop of this shape sustains at best
+        tile = {}
+        tsrc = inputs[0]["k"]
+        for name, parts in (("k_fragment_reads", 1), ("v_fragment_reads", 2), ("direct_loads", 4), ("reads_and_loads", 7),
+                            ("mfma_register_operands", 8), ("mfma_fed_by_reads", 11), ("mfma_fed_by_reads_and_loads", 15)):
+            svoo.microbench_attn_tile(parts, 200, tsrc, sink[:512 * 256])
+            torch.cuda.synchronize()
+            m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            m0.record()
+            svoo.microbench_attn_tile(parts, 4000, tsrc, sink[:512 * 256])
+            m1.record()
+            torch.cuda.synchronize()
+            tile[name + "_ns"] = round(m0.elapsed_time(m1) * 1e6 / 4000, 1)
+        # one tile round of a CU = 256 query rows x 64 keys = 256 matrix instructions on each of 256 CUs
+        tile["ceiling_tflops_without_softmax"] = round(256 * 256 * 2.0 * 32 * 32 * 16 / tile["mfma_fed_by_reads_and_loads_ns"] / 1e3, 1)
+        tile["unit"] = "ns per tile round of a CU (2 workgroups x 128 query rows x 64 keys, d=128, tile data out of L2)"
+        measured["attn_tile_skeleton"] = tile
         print(f"[bench] measured peaks: {measured}", file=sys.stderr, flush=True)
 
     attn_ms = step_ms[:, 3]

@@ -298,7 +298,17 @@ int svoo_attention_density(const svoo_shape* shape, const void* q, const void* k
  *
  * svoo_microbench_copy: dst[0..bytes) = src[0..bytes) (device, 16-byte aligned, bytes a multiple
  * of 16, no overlap) with plain 16-byte loads and stores; moves 2 x bytes.
+ *
+ * svoo_microbench_attn_tile: what one 64-key tile step of the bf16 attention kernel (d = 128, 4 waves x 32
+ * query rows, two workgroups per CU, 512 workgroups in all) moves through the LDS, without the softmax:
+ * per wave 16 K fragment reads, 32 transposing V fragment reads, 8 direct global->LDS loads of 1 KB out of
+ * L2 and the 32 matrix instructions they feed -- the subset in `parts` (bit 0 K reads, 1 V reads, 2 direct
+ * loads, 3 matrix instructions; instantiated: 1, 2, 3, 4, 7, 8, 11, 15), `iters` steps with one barrier
+ * each.  src (device, 16-byte aligned, at least 4 MiB + 64 KiB readable): tile data, e.g. a K tensor;
+ * sink (device) [512 * 256] float.  Launch time / iters = time of one tile round of a CU (256 query rows
+ * x 64 keys = 256 matrix instructions = 8.39 MFLOP).
  */
+int svoo_microbench_attn_tile(int32_t parts, int32_t iters, const void* src, float* sink, void* hip_stream);
 int svoo_microbench_mfma_bf16(int32_t workgroups, int32_t iters, int32_t random_operands, float* sink,
                               double* flops, void* hip_stream);
 int svoo_microbench_copy(const void* src, void* dst, size_t bytes, void* hip_stream);

@@ -57,6 +57,7 @@ _SIGNATURES = {
     "svoo_attention_density": (ctypes.c_int, [_SP, _vp, _vp, _vp, _i32, _f32, _f32, _vp, _vp, _vp, _vp]),
     "svoo_microbench_mfma_bf16": (ctypes.c_int, [_i32, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
     "svoo_microbench_copy": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
+    "svoo_microbench_attn_tile": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -411,6 +412,15 @@ def microbench_mfma_bf16(sink, iters, random_operands=True):
                                           ctypes.byref(flops), _stream())
     _run(st, "svoo_microbench_mfma_bf16")
     return flops.value
+
+
+def microbench_attn_tile(parts: int, iters: int, src, sink):
+    """svoo_microbench_attn_tile: the LDS traffic (and matrix instructions) of one attention tile step; the
+    caller times the launch.  src: device tensor of at least 4 MiB + 64 KiB, sink: float32 [512 * 256]."""
+    _check(sink, torch.float32, (512 * 256,), "sink")
+    if src.numel() * src.element_size() < (4 << 20) + (64 << 10):
+        raise ValueError("src too small")
+    _run(_lib().svoo_microbench_attn_tile(parts, iters, _ptr(src), _ptr(sink), _stream()), "svoo_microbench_attn_tile")
 
 
 def microbench_copy(src, dst):

@@ -136,6 +136,8 @@ def test_entry_points_reject_bad_arguments_on_host(lib):
     assert lib.svoo_microbench_copy(fake, ctypes.c_void_p(0x2000), 24, null) == INVALID       # not a multiple of 16
     assert lib.svoo_microbench_copy(odd, ctypes.c_void_p(0x2000), 32, null) == INVALID
     assert lib.svoo_microbench_copy(fake, null, 32, null) == INVALID
+    assert lib.svoo_microbench_attn_tile(5, 10, fake, fake, null) == INVALID                 # subset not instantiated
+    assert lib.svoo_microbench_attn_tile(1, 0, fake, fake, null) == INVALID
 
 
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):

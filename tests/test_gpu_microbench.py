@@ -31,3 +31,17 @@ def test_mfma_loop_reports_its_flops(random_operands):
     if not random_operands:
         # every operand is 0.125: each accumulator holds 4 instructions x 50 iterations x 16 products
         assert torch.all(sink == 4 * 16 * 200 * 16 * 0.125 * 0.125)
+
+
+def test_attention_tile_skeleton_runs_every_instantiated_subset():
+    """The LDS-path microbenchmark launches, finishes and rejects the subsets it does not instantiate."""
+    src = torch.randn((3 << 20,), device="cuda:0").to(torch.bfloat16)        # 6 MiB of tile-like data
+    sink = torch.zeros((512 * 256,), dtype=torch.float32, device="cuda:0")
+    for parts in (1, 2, 3, 4, 7, 8, 11, 15):
+        svoo.microbench_attn_tile(parts, 3, src, sink)
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all()
+    with pytest.raises(svoo.SvooError):
+        svoo.microbench_attn_tile(5, 3, src, sink)
+    with pytest.raises(ValueError):
+        svoo.microbench_attn_tile(1, 3, src[:1000], sink)

@@ -672,11 +672,13 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     constexpr int RPL = 64 / CPR;            // rows per wave-load
     constexpr int LPW = (32 / RPL) / 4;      // wave-loads per wave for one half block
     __shared__ __attribute__((aligned(1024))) unsigned char wl[2 * 2 * HALF];   // [buf][hi|lo][32][ROWB]
-    const int b = blockIdx.y, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
+    const int b = blockIdx.y, tid = threadIdx.x, lane = tid % 64, j = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);     // uniform: what derives from it stays scalar
     const int t0 = blockIdx.x * 256 + 64 * wave;
     const unsigned char* whb = (const unsigned char*)whi + (size_t)b * k_own * ROWB;
     const unsigned char* wlb = (const unsigned char*)wlo + (size_t)b * k_own * ROWB;
     const int n_blocks = (k_own + 31) / 32;
+    const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(wl));
 
     auto issue_block = [&](int cb, int buf) {
 #pragma unroll
@@ -686,9 +688,9 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
             row = row < k_own ? row : k_own - 1;
             const int chunk = (lane % CPR) ^ (rl % CPR);
             const uint32_t goff = (uint32_t)row * ROWB + chunk * 16;
-            const int loff = buf * 2 * HALF + (wave * LPW + i) * RPL * ROWB;
-            load_global_to_lds_16(whb + goff, lds_address(wl) + loff);
-            load_global_to_lds_16(wlb + goff, lds_address(wl) + loff + HALF);
+            const uint32_t loff = lds0 + buf * 2 * HALF + (wave * LPW + i) * RPL * ROWB;
+            load_rows_to_lds_16(goff, whb, loff);
+            load_rows_to_lds_16(goff, wlb, loff + HALF);
         }
     };
     issue_block(0, 0);
@@ -728,7 +730,7 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
         for (int c = 0; c < DC; ++c) asm volatile("" ::"v"(xf[tb][c]));
 
     float best[2] = {-INFINITY, -INFINITY}, second[2] = {-INFINITY, -INFINITY};
-    int bidx[2] = {0, 0};
+    int bidx[2] = {0, 0}, lidx[2] = {0, 0};
     for (int cb = 0; cb < n_blocks; ++cb) {
         const int buf = cb & 1;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -750,28 +752,49 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
                 acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, xf[tb][c], acc[tb], 0, 0, 0);
             }
         }
-        const int cbase = 32 * cb + 4 * h;
-        float bias[16];
+        const int cbase = 32 * cb;      // uniform; the lane's own offset 4 h is added to the winner once, after the loop
         if (BIAS) {
-            const float4* hb = (const float4*)(half_sq + (size_t)b * (32 * n_blocks) + cbase);
+            const float4* hb = (const float4*)(half_sq + (size_t)b * (32 * n_blocks) + cbase + 4 * h);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const float4 t = hb[2 * g];
-                bias[4 * g] = t.x; bias[4 * g + 1] = t.y; bias[4 * g + 2] = t.z; bias[4 * g + 3] = t.w;
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) {
+                    acc[tb][4 * g] -= t.x;
+                    acc[tb][4 * g + 1] -= t.y;
+                    acc[tb][4 * g + 2] -= t.z;
+                    acc[tb][4 * g + 3] -= t.w;
+                }
             }
         }
+        if (cbase + 32 > k_own) {       // only the last block can hold centroids past the end: they never win
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
+            for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int cl = cbase + 8 * (v / 4) + (v % 4);
-                const float sc = BIAS ? acc[tb][v] - bias[v] : acc[tb][v];
-                const float val = cl < k_own ? sc : -INFINITY;
+                for (int v = 0; v < 16; ++v)
+                    if (cbase + 4 * h + 8 * (v / 4) + (v % 4) >= k_own) acc[tb][v] = -INFINITY;
+        }
+        // best, second best and the winner: one median, one compare and two selects per score (selects instead
+        // of a maximum keep the compiler from canonicalising every score first).  Inside the block only the
+        // winner's position in the block is tracked (a small constant per score); the centroid index is
+        // updated once per block, if the best moved.  The two token groups are independent chains and are
+        // interleaved so that no select waits on its compare.
+        float before[2] = {best[0], best[1]};
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const float val = acc[tb][v];
                 second[tb] = __builtin_amdgcn_fmed3f(best[tb], second[tb], val);
-                bidx[tb] = val > best[tb] ? cl : bidx[tb];
-                best[tb] = fmaxf(best[tb], val);
+                const bool up = val > best[tb];
+                lidx[tb] = up ? 8 * (v / 4) + (v % 4) : lidx[tb];
+                best[tb] = up ? val : best[tb];
             }
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) bidx[tb] = best[tb] > before[tb] ? cbase + lidx[tb] : bidx[tb];
     }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) bidx[tb] += 4 * h;
     const float wmax = __int_as_float(wmax_bits[b]);
     const bool degenerate = flags[b] != 0;
 #pragma unroll

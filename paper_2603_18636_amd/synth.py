@@ -104,15 +104,29 @@ def layer_keeps(cfg: Config) -> np.ndarray:
     return rng.uniform(lo, hi, size=cfg.n_layers).astype(np.float32)
 
 
-# Heads may be drawn by several threads at once (make_layer).  Concurrent calls into the BLAS behind
-# numpy's matmul have returned corrupted rows now and then, so every matrix product takes this lock
-# (the products are a small part of the work: the normal draws and sin/cos dominate).
+# Heads may be drawn by several threads at once (make_layer), and the draw must not depend on that.  A
+# BLAS product of a tall matrix does: OpenBLAS splits the rows among however many of its workers are
+# free at that moment, rows that fall into a remainder panel are summed in another order (differences
+# of a few 1e-14), and the single rounding to bf16 turns some of those into different inputs.  So the
+# tall products (N rows, inner dimension 3, 16 or d) are written as a fixed-order sum of rank-1 terms
+# (`_rowmix`), and only the two d x d Gram matrices of the scale computation go through BLAS, whose
+# reduction over the N rows is done by one thread per output element in a fixed blocking (`_mm`; the
+# lock keeps concurrent callers from sharing the worker pool all the same).
 _MATMUL_LOCK = threading.Lock()
 
 
 def _mm(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     with _MATMUL_LOCK:
         return a @ b
+
+
+def _rowmix(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """a @ b for a tall a [N, c] and a small inner dimension c, as sum_c a[:, c] b[c] added in index order:
+    every row is computed the same way whatever else runs at the same time."""
+    out = a[:, 0:1] * b[0]
+    for c in range(1, a.shape[1]):
+        out += a[:, c:c + 1] * b[c]
+    return out
 
 
 def grid_positions(grid: Tuple[int, int, int]) -> np.ndarray:
@@ -195,10 +209,10 @@ def make_head(cfg: Config, layer: int, head: int, grid: Optional[Tuple[int, int,
     freqs = rng.standard_normal((8, 3)) * 2.0
     f_q = rng.standard_normal((16, d)) / 4.0
     f_k = rng.standard_normal((16, d)) / 4.0
-    ang = 2.0 * math.pi * _mm(u, freqs.T)
+    ang = 2.0 * math.pi * _rowmix(u, freqs.T)
     phi = np.concatenate([np.sin(ang), np.cos(ang)], axis=1)
-    q = _mm(z, m_q)[region] + _mm(phi, f_q) + 0.3 * rng.standard_normal((n, d))
-    k = _mm(z, m_k)[region] + _mm(phi, f_k) + 0.3 * rng.standard_normal((n, d))
+    q = _rowmix(z, m_q)[region] + _rowmix(phi, f_q) + 0.3 * rng.standard_normal((n, d))
+    k = _rowmix(z, m_k)[region] + _rowmix(phi, f_k) + 0.3 * rng.standard_normal((n, d))
     v = rng.standard_normal((n, d))
     var = logit_row_variance(q, k)
     gamma = (9.0 / var) ** 0.25

@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # a copy of known size gives, plus WRITE_SIZE; profiles/sparse_attn_config2_pmc.txt).  Counters cannot be read
 # from inside this program, so the figure is an offline one and carries the keep ratio it was taken at; it is
 # reported only when the run's own keep ratio matches (the fixed keep 0.2 leg).
-MEASURED_TRAFFIC = {2: {"keep": 0.2, "bytes_past_l2": None, "l2_hit_rate": None}}
+MEASURED_TRAFFIC = {2: {"keep": 0.2, "bytes_past_l2": 2.896e7 * 1024 * 1.97 + 226800 * 1024, "l2_hit_rate": 0.234}}
 STEP_NAMES = ("cocluster", "permute", "block_mask", "sparse_attn", "unpermute")
 
 

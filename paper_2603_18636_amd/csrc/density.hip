@@ -19,14 +19,18 @@
 //
 // bf16 inputs: S^T = K Q^T on v_mfma_f32_32x32x16_bf16, one query per lane column, 128 query rows
 // per workgroup, K in 64-key LDS tiles filled by direct global->LDS loads (same swizzle as the
-// attention kernel), three buffers.  float32 inputs: a plain kernel, one workgroup per row.
+// attention kernel).  A row sample that yields fewer workgroups than the chip has compute units
+// (the offline profiling samples rows) would leave one wave per SIMD with nothing to hide its
+// latencies behind: such launches split the keys KS ways inside the workgroup (4 KS waves, wave
+// (rg, ks) takes the tiles ks, ks + KS, ... for row group rg) and combine the KS partial results
+// of a pass through LDS in the fixed order ks = 0, 1, ...  float32 inputs: a plain kernel, one
+// workgroup per row.
 #include <type_traits>
 
 #include "common.h"
 
 #define LOG2E_F 1.4426950408889634f
 #define DEN_KT 64
-#define DEN_NBUF 3
 #define DEN_MAX_PASSES 48   // 2 + at most ~34 halvings of a float interval; a hard stop
 
 typedef __attribute__((ext_vector_type(8))) __bf16 den_bf16x8;
@@ -116,35 +120,52 @@ __device__ __forceinline__ int row_state_result(const RowState& r, float c2, int
     return len < 1 ? 1 : (len > n ? n : len);
 }
 
-template <int D>
-__global__ void __launch_bounds__(256)
+// per-row partial result of one pass, one per key split
+struct PassPartial {
+    float mx, mn;
+    int cnt, pad;
+    double mass;
+};
+
+template <int D, int KS, int NBUF>
+static constexpr size_t density_lds_bytes() {
+    return (size_t)NBUF * KS * DEN_KT * D * 2 + (KS > 1 ? (size_t)KS * 128 * sizeof(PassPartial) : 0);
+}
+
+template <int D, int KS, int NBUF>
+__global__ void __launch_bounds__(256 * KS)
 density_bf16_kernel(DensityArgs a) {
-    constexpr int DC = D / 16, CPR = D / 8, ROWB = D * 2, TILE = DEN_KT * ROWB;
+    constexpr int DC = D / 16, CPR = D / 8, ROWB = D * 2, TILE = DEN_KT * ROWB, STAGE = KS * TILE;
     constexpr int RPL = 64 / CPR;             // tile rows covered by one wave-load (1 KB)
-    constexpr int LPW = (DEN_KT / 4) / RPL;   // wave-loads per wave and tile
-    __shared__ __attribute__((aligned(1024))) unsigned char k_lds[DEN_NBUF * TILE];
-    const int b = blockIdx.y, tid = threadIdx.x, wave = tid / 64, lane = tid % 64, j = lane % 32, h = lane / 32;
+    constexpr int LPW = (DEN_KT / 4) / RPL;   // wave-loads per wave and step (a quarter of one tile)
+    static_assert(NBUF == 2 || NBUF == 3, "two or three stages");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char k_lds[];
+    const int b = blockIdx.y, tid = threadIdx.x, lane = tid % 64, j = lane % 32, h = lane / 32;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64), rg = wave % 4, ks = wave / 4;
     const int n = a.n;
-    const int ridx = blockIdx.x * 128 + 32 * wave + j;
+    const int rloc = 32 * rg + j;
+    const int ridx = blockIdx.x * 128 + rloc;
     const bool rvalid = ridx < a.n_rows;
     int qrow = rvalid ? (a.rows ? a.rows[ridx] : ridx) : 0;
     qrow = qrow < 0 ? 0 : (qrow >= n ? n - 1 : qrow);
     const unsigned char* kg = (const unsigned char*)a.k + (size_t)b * n * ROWB;
     const int n_tiles = (n + DEN_KT - 1) / DEN_KT;
+    const int n_steps = (n_tiles + KS - 1) / KS;     // a step = KS tiles, one per key split
 
-    auto issue = [&](int kt, int buf) {
+    // wave (rg, ks) fetches quarter rg of the tile its key split consumes in step `step`
+    auto issue = [&](int step, int buf) {
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int rl = (wave * LPW + i) * RPL + lane / CPR;     // tile row
-            int row = kt * DEN_KT + rl;
-            row = row < n ? row : n - 1;                            // rows past the end are masked later
+            const int rl = (rg * LPW + i) * RPL + lane / CPR;       // tile row
+            int row = (step * KS + ks) * DEN_KT + rl;
+            row = row < n ? row : n - 1;                            // rows past the end are masked or unused
             const int chunk = (lane % CPR) ^ (rl % CPR);
             load_global_to_lds_16(kg + (size_t)row * ROWB + chunk * 16,
-                                  lds_address(k_lds) + buf * TILE + (wave * LPW + i) * RPL * ROWB);
+                                  lds_address(k_lds) + buf * STAGE + ks * TILE + (rg * LPW + i) * RPL * ROWB);
         }
     };
-    issue(0, 0);
-    issue(1 % n_tiles, 1);
+#pragma unroll
+    for (int p = 0; p < NBUF - 1; ++p) issue(p % n_steps, p);
 
     den_bf16x8 qf[DC];
     {
@@ -165,56 +186,59 @@ density_bf16_kernel(DensityArgs a) {
     float mx = -INFINITY, mn = INFINITY;
     double mass = 0.0;
     int cnt = 0;
-    int pass = 0, kt = 0;
-    // tiles are consumed in one running sequence g = pass * n_tiles + kt; tile g sits in buffer
-    // g % 3 and tiles g + 1, g + 2 are in flight or landed
+    int pass = 0, step = 0;
+    // steps are consumed in one running sequence g = pass * n_steps + step; step g sits in stage
+    // g % NBUF and the next NBUF - 1 steps are in flight or landed
     for (int g = 0;; ++g) {
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW) : "memory");   // all but the newest tile's loads
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPW * (NBUF - 2)) : "memory");   // all but the newest steps' loads
         __syncthreads();
         {
-            int nk = kt + 2;
-            nk = nk >= n_tiles ? nk % n_tiles : nk;      // wraps into the next pass (n_tiles may be 1 or 2)
-            issue(nk, (g + 2) % DEN_NBUF);
+            int ns = step + NBUF - 1;
+            ns = ns >= n_steps ? ns % n_steps : ns;      // wraps into the next pass (n_steps may be 1 or 2)
+            issue(ns, (g + NBUF - 1) % NBUF);
         }
-        const unsigned char* base = k_lds + (g % DEN_NBUF) * TILE;
-        den_f32x16 s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-        for (int c = 0; c < DC; ++c) {
-            const den_bf16x8 a0 = __builtin_bit_cast(den_bf16x8, *(const uint4*)(base + koff[c]));
-            const den_bf16x8 a1 = __builtin_bit_cast(den_bf16x8, *(const uint4*)(base + 32 * ROWB + koff[c]));
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[c], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[c], s[1], 0, 0, 0);
-        }
-        const bool ragged = kt == n_tiles - 1 && (n % DEN_KT) != 0;
-        if (pass == 0) {
+        const int kt = step * KS + ks;
+        if (kt < n_tiles) {
+            const unsigned char* base = k_lds + (g % NBUF) * STAGE + ks * TILE;
+            den_f32x16 s[2];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const bool valid = !ragged || kt * DEN_KT + 32 * kb + 8 * (v / 4) + 4 * h + (v % 4) < n;
-                    mx = fmaxf(mx, valid ? s[kb][v] : -INFINITY);
-                    mn = fminf(mn, valid ? s[kb][v] : INFINITY);
-                }
-        } else {
-            float ts = 0.f;
+                for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int c = 0; c < DC; ++c) {
+                const den_bf16x8 a0 = __builtin_bit_cast(den_bf16x8, *(const uint4*)(base + koff[c]));
+                const den_bf16x8 a1 = __builtin_bit_cast(den_bf16x8, *(const uint4*)(base + 32 * ROWB + koff[c]));
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[c], s[0], 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[c], s[1], 0, 0, 0);
+            }
+            const bool ragged = kt == n_tiles - 1 && (n % DEN_KT) != 0;
+            if (pass == 0) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const bool valid = !ragged || kt * DEN_KT + 32 * kb + 8 * (v / 4) + 4 * h + (v % 4) < n;
-                    const float sv = s[kb][v];
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sv, c2, st.nmb));
-                    const bool ge = valid && sv >= st.thr;
-                    ts += ge ? p : 0.f;
-                    cnt += ge ? 1 : 0;
-                }
-            mass += (double)ts;
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const bool valid = !ragged || kt * DEN_KT + 32 * kb + 8 * (v / 4) + 4 * h + (v % 4) < n;
+                        mx = fmaxf(mx, valid ? s[kb][v] : -INFINITY);
+                        mn = fminf(mn, valid ? s[kb][v] : INFINITY);
+                    }
+            } else {
+                float ts = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const bool valid = !ragged || kt * DEN_KT + 32 * kb + 8 * (v / 4) + 4 * h + (v % 4) < n;
+                        const float sv = s[kb][v];
+                        const float p = __builtin_amdgcn_exp2f(fmaf(sv, c2, st.nmb));
+                        const bool ge = valid && sv >= st.thr;
+                        ts += ge ? p : 0.f;
+                        cnt += ge ? 1 : 0;
+                    }
+                mass += (double)ts;
+            }
         }
-        if (++kt == n_tiles) {
+        if (++step == n_steps) {
             // both half-waves hold half of each row's keys: exchange and combine
             {
                 auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(mx), __float_as_int(mx), false, false);
@@ -231,18 +255,56 @@ density_bf16_kernel(DensityArgs a) {
                 const double m1 = __longlong_as_double(((long long)(int)rh[1] << 32) | (unsigned int)rl[1]);
                 mass = m0 + m1;      // (own, other) in one half, (other, own) in the other: same sum
             }
+            if constexpr (KS > 1) {
+                // the key splits of a row group exchange their partial results; every wave then adds
+                // them in the order ks = 0, 1, ..., so all of them step the same row state
+                PassPartial* part = (PassPartial*)(k_lds + (size_t)NBUF * STAGE);
+                if (h == 0) part[ks * 128 + rloc] = PassPartial{mx, mn, cnt, 0, mass};
+                __syncthreads();
+                PassPartial t = part[rloc];
+#pragma unroll
+                for (int o = 1; o < KS; ++o) {
+                    const PassPartial u = part[o * 128 + rloc];
+                    t.mx = fmaxf(t.mx, u.mx);
+                    t.mn = fminf(t.mn, u.mn);
+                    t.cnt += u.cnt;
+                    t.mass += u.mass;
+                }
+                mx = t.mx; mn = t.mn; cnt = t.cnt; mass = t.mass;
+            }
             row_state_step(st, pass, mx, mn, mass, cnt, c2, a.tau);
             mass = 0.0;
             cnt = 0;
-            kt = 0;
+            step = 0;
             ++pass;
+            // also orders this pass's reads of the partial results before the next pass's writes
             const int all_done = __syncthreads_and((st.done || !rvalid) ? 1 : 0);
             if (all_done || pass >= DEN_MAX_PASSES) break;
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // loads issued for the pass that never ran
     if (a.passes && tid == 0) atomicMax(&a.passes[b], pass);
-    if (rvalid && h == 0) a.prefix_len[(size_t)b * a.n_rows + ridx] = row_state_result(st, c2, n);
+    if (rvalid && h == 0 && ks == 0) a.prefix_len[(size_t)b * a.n_rows + ridx] = row_state_result(st, c2, n);
+}
+
+template <int D, int KS, int NBUF>
+static int launch_density_bf16(const DensityArgs& a, int bh, hipStream_t stream) {
+    static unsigned char opted_in[SVOO_MAX_DEVICES];
+    constexpr int lds = (int)density_lds_bytes<D, KS, NBUF>();
+    auto kern = density_bf16_kernel<D, KS, NBUF>;
+    if (!opt_in_dynamic_lds((const void*)kern, lds, opted_in)) return SVOO_ERR_HIP;
+    hipLaunchKernelGGL(kern, dim3((a.n_rows + 127) / 128, bh), dim3(256 * KS), lds, stream, a);
+    return SVOO_OK;
+}
+
+// Fewer workgroups than the chip can hold at one per compute unit (or two): split the keys inside
+// the workgroup so that every SIMD still has several waves.
+template <int D>
+static int dispatch_density_bf16(const DensityArgs& a, int bh, hipStream_t stream) {
+    const long long wgs = (long long)((a.n_rows + 127) / 128) * bh;
+    if (wgs <= 256) return launch_density_bf16<D, 4, 2>(a, bh, stream);
+    if (wgs <= 512) return launch_density_bf16<D, 2, 2>(a, bh, stream);
+    return launch_density_bf16<D, 1, 3>(a, bh, stream);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -344,11 +406,9 @@ extern "C" int svoo_attention_density(const svoo_shape* shape, const void* q, co
     if (passes)
         hipLaunchKernelGGL(density_clear_kernel, dim3((shape->bh + 255) / 256), dim3(256), 0, stream, passes, shape->bh);
     if (shape->dtype == SVOO_BF16) {
-        dim3 grid((n_rows + 127) / 128, shape->bh);
-        if (shape->d == 128)
-            hipLaunchKernelGGL(density_bf16_kernel<128>, grid, dim3(256), 0, stream, a);
-        else
-            hipLaunchKernelGGL(density_bf16_kernel<64>, grid, dim3(256), 0, stream, a);
+        st = shape->d == 128 ? dispatch_density_bf16<128>(a, shape->bh, stream)
+                             : dispatch_density_bf16<64>(a, shape->bh, stream);
+        if (st != SVOO_OK) return st;
     } else {
         dim3 grid(n_rows, shape->bh);
         if (shape->d == 128)

@@ -49,6 +49,36 @@ def test_density_matches_oracle(dtype, d, grid, tau):
             assert abs(dens[b] - ref["density"]) <= 1e-14
 
 
+@pytest.mark.parametrize("d,grid,copies", [(128, (6, 12, 20), 12), (128, (6, 12, 20), 24), (64, (3, 3, 37), 45),
+                                           (64, (3, 3, 37), 90), (128, (1, 3, 43), 300)])
+def test_density_in_every_launch_shape(d, grid, copies):
+    """The bf16 kernel splits the keys 4, 2 or 1 ways inside a workgroup depending on how many
+    workgroups the launch has (<= 256, <= 512, more); the small cases above all take the 4-way shape.
+    Here two heads are repeated ``copies`` times so that the same data runs through the other shapes
+    (n = 1440: 12 workgroups per head -> 288 and 576; n = 333, ragged last tile: 3 per head -> 270 and
+    540; n = 129: 2 per head, three 64-key tiles of which the last holds one key -> 1200), each
+    compared with the oracle, and every copy must equal the first."""
+    cfg = synth.CONFIGS[1]
+    heads = [synth.make_head(cfg, 7, hd, grid=grid, n_seeds=8, kq=1, kk=1, d=d, dtype="bf16") for hd in range(2)]
+    q = np.tile(np.stack([h["q"] for h in heads]), (copies, 1, 1))
+    k = np.tile(np.stack([h["k"] for h in heads]), (copies, 1, 1))
+    n = q.shape[1]
+    wgs = (n + 127) // 128 * 2 * copies
+    assert wgs > 256
+    scale, tau32 = H.scale_of(d), float(np.float32(0.95))
+    plen, dens, passes = svoo.attention_density(H.to_dev(q, "bf16"), H.to_dev(k, "bf16"), tau32, scale, want_passes=True)
+    plen, dens, passes = H.to_np(plen), H.to_np(dens), H.to_np(passes)
+    for b in range(2):
+        ref = so.attention_density(q[b], k[b], scale, tau32)
+        compare_prefix(plen[b], ref, max_near=max(2, n // 100))
+        assert (plen[b::2] == plen[b]).all() and (dens[b::2] == dens[b]).all() and (passes[b::2] == passes[b]).all()
+    # the 4-way shape on the same two heads
+    plen4, _ = svoo.attention_density(H.to_dev(q[:2], "bf16"), H.to_dev(k[:2], "bf16"), tau32, scale)
+    differ = int((H.to_np(plen4) != plen[:2]).sum())
+    print(f"{wgs} workgroups: {differ} of {2 * n} prefix lengths differ from the 4-way launch")
+    assert differ <= max(2, n // 100)
+
+
 def test_density_row_subset_and_order():
     h = synth.make_head(synth.CONFIGS[1], 5, 0, grid=(6, 12, 20), n_seeds=8, kq=1, kk=1)
     q, k, n = h["q"][None], h["k"][None], h["q"].shape[0]

@@ -47,12 +47,20 @@ __device__ __forceinline__ void load_pair<float>(const float* p, double& a, doub
     b = (double)u.y;
 }
 
+// The per-slice words the next assignment accumulates into (degenerate flag, largest row norm, queue
+// length) are cleared by the kernel that precedes it in the stream, not by a launch of their own.
+__device__ __forceinline__ void clear_words(int32_t* clear, int clear_n) {
+    if (clear && blockIdx.x == 0 && blockIdx.y == 0)
+        for (int i = threadIdx.x; i < clear_n; i += blockDim.x) clear[i] = 0;
+}
+
 // c64[b, c, :] = x[b, idx[b, c], :]   or   c64 = (double) init_c
 template <typename T>
 __global__ void init_centroids_kernel(const T* __restrict__ x, const int32_t* __restrict__ idx,
                                       const float* __restrict__ init_c, double* __restrict__ c64, int n, int k,
-                                      int d) {
+                                      int d, int32_t* __restrict__ clear, int clear_n) {
     const int b = blockIdx.y, c = blockIdx.x, t = threadIdx.x;
+    clear_words(clear, clear_n);
     if (t >= d) return;
     double v;
     if (init_c) {
@@ -852,7 +860,8 @@ template <typename T, int D>
 __global__ void __launch_bounds__(256)
 centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm,
                        const int32_t* __restrict__ offsets, double* __restrict__ c64, float* __restrict__ c32,
-                       int32_t* __restrict__ counts, int n, int k) {
+                       int32_t* __restrict__ counts, int n, int k, int32_t* __restrict__ clear, int clear_n) {
+    clear_words(clear, clear_n);
     constexpr int LANES = D / 8;
     constexpr int GROUPS = 256 / LANES;
     __shared__ double part[GROUPS][D];
@@ -894,23 +903,25 @@ centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm
     if (threadIdx.x == 0 && counts) counts[(size_t)b * k + j] = cnt;
 }
 
+// clear / clear_n: words to zero for the assignment that follows in the stream (nullable)
 static void launch_centroid_update(const svoo_shape* s, const void* x, const int32_t* perm, const int32_t* offsets,
-                                   double* c64, float* c32, int32_t* counts, int k, hipStream_t stream) {
+                                   double* c64, float* c32, int32_t* counts, int k, int32_t* clear, int clear_n,
+                                   hipStream_t stream) {
     dim3 grid(k, s->bh);
     if (s->dtype == SVOO_BF16) {
         if (s->d == 128)
             hipLaunchKernelGGL((centroid_update_kernel<uint16_t, 128>), grid, dim3(256), 0, stream, (const uint16_t*)x,
-                               perm, offsets, c64, c32, counts, s->n, k);
+                               perm, offsets, c64, c32, counts, s->n, k, clear, clear_n);
         else
             hipLaunchKernelGGL((centroid_update_kernel<uint16_t, 64>), grid, dim3(256), 0, stream, (const uint16_t*)x,
-                               perm, offsets, c64, c32, counts, s->n, k);
+                               perm, offsets, c64, c32, counts, s->n, k, clear, clear_n);
     } else {
         if (s->d == 128)
             hipLaunchKernelGGL((centroid_update_kernel<float, 128>), grid, dim3(256), 0, stream, (const float*)x, perm,
-                               offsets, c64, c32, counts, s->n, k);
+                               offsets, c64, c32, counts, s->n, k, clear, clear_n);
         else
             hipLaunchKernelGGL((centroid_update_kernel<float, 64>), grid, dim3(256), 0, stream, (const float*)x, perm,
-                               offsets, c64, c32, counts, s->n, k);
+                               offsets, c64, c32, counts, s->n, k, clear, clear_n);
     }
 }
 
@@ -1036,11 +1047,14 @@ size_t cluster_ws_bytes(const svoo_shape* s) { return carve_cluster_ws(s, nullpt
 
 // One half-step's assignment: labels of x against own-side centroids through opp-side anchors.
 // want_nx2: also fill w.nx2 (needed for the objective) even if no anchor is degenerate.
+// words_cleared: the preceding kernel of the stream has zeroed w.flags / wmax_bits / list_count.
 static int assign_side(const svoo_shape* s, const ClusterWs& w, const void* x, const double* c_own, int k_own,
-                       const double* c_opp, int k_opp, int32_t* labels, bool want_nx2, hipStream_t stream) {
+                       const double* c_opp, int k_opp, int32_t* labels, bool want_nx2, bool words_cleared,
+                       hipStream_t stream) {
     const int d = s->d, bh = s->bh;
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((3 * bh + 255) / 256), dim3(256), 0, stream, w.flags, 0,
-                       (size_t)3 * bh);
+    if (!words_cleared)
+        hipLaunchKernelGGL(fill_i32_kernel, dim3((3 * bh + 255) / 256), dim3(256), 0, stream, w.flags, 0,
+                           (size_t)3 * bh);
     // W = Norm(C_own C_opp^T) C_opp with b_j and the degenerate flags; for bf16 tokens also the split of W,
     // its transpose and the largest row norm for the matrix-core pre-filter
     {
@@ -1099,14 +1113,14 @@ static void launch_objective(const svoo_shape* s, const ClusterWs& w, const void
 }
 
 static void launch_init_centroids(const svoo_shape* s, const void* x, const int32_t* idx, const float* init_c,
-                                  double* c64, int k, hipStream_t stream) {
+                                  double* c64, int k, int32_t* clear, int clear_n, hipStream_t stream) {
     dim3 grid(k, s->bh);
     if (s->dtype == SVOO_BF16)
         hipLaunchKernelGGL(init_centroids_kernel<uint16_t>, grid, dim3(128), 0, stream, (const uint16_t*)x, idx, init_c,
-                           c64, s->n, k, s->d);
+                           c64, s->n, k, s->d, clear, clear_n);
     else
         hipLaunchKernelGGL(init_centroids_kernel<float>, grid, dim3(128), 0, stream, (const float*)x, idx, init_c, c64,
-                           s->n, k, s->d);
+                           s->n, k, s->d, clear, clear_n);
 }
 
 // perm_* / *_offsets (all four or none): the cluster-order layout of the returned labels, which the
@@ -1128,12 +1142,13 @@ static int cocluster_impl(const svoo_shape* shape, const void* q, const void* k,
     if (ws_bytes < w.bytes) return SVOO_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    launch_init_centroids(shape, q, init_q_idx, init_cq, w.c64q, shape->kq, stream);
-    launch_init_centroids(shape, k, init_k_idx, init_ck, w.c64k, shape->kk, stream);
+    launch_init_centroids(shape, q, init_q_idx, init_cq, w.c64q, shape->kq, nullptr, 0, stream);
+    launch_init_centroids(shape, k, init_k_idx, init_ck, w.c64k, shape->kk, w.flags, 3 * shape->bh, stream);
     for (int it = 0; it < iters; ++it) {
         const bool last = it == iters - 1;
         // Step A: keys against query anchors (old C_q), own centroids old C_k.
-        st = assign_side(shape, w, k, w.c64k, shape->kk, w.c64q, shape->kq, labels_k, objective != nullptr, stream);
+        st = assign_side(shape, w, k, w.c64k, shape->kk, w.c64q, shape->kq, labels_k, objective != nullptr, true,
+                         stream);
         if (st != SVOO_OK) return st;
         if (objective)
             launch_objective(shape, w, k, shape->kk, labels_k, objective + (size_t)it * 2, iters * 2, stream);
@@ -1142,9 +1157,10 @@ static int cocluster_impl(const svoo_shape* shape, const void* q, const void* k,
         st = sort_labels(shape->bh, shape->n, shape->kk, labels_k, pk, ok, nullptr, w.chunk_hist, stream);
         if (st != SVOO_OK) return st;
         launch_centroid_update(shape, k, pk, ok, w.c64k, last ? ck : nullptr, last ? counts_k : nullptr, shape->kk,
-                               stream);
+                               w.flags, 3 * shape->bh, stream);
         // Step B: queries against the NEW key anchors, own centroids the OLD C_q.
-        st = assign_side(shape, w, q, w.c64q, shape->kq, w.c64k, shape->kk, labels_q, objective != nullptr, stream);
+        st = assign_side(shape, w, q, w.c64q, shape->kq, w.c64k, shape->kk, labels_q, objective != nullptr, true,
+                         stream);
         if (st != SVOO_OK) return st;
         if (objective)
             launch_objective(shape, w, q, shape->kq, labels_q, objective + (size_t)it * 2 + 1, iters * 2, stream);
@@ -1153,7 +1169,7 @@ static int cocluster_impl(const svoo_shape* shape, const void* q, const void* k,
         st = sort_labels(shape->bh, shape->n, shape->kq, labels_q, pq, oq, nullptr, w.chunk_hist, stream);
         if (st != SVOO_OK) return st;
         launch_centroid_update(shape, q, pq, oq, w.c64q, last ? cq : nullptr, last ? counts_q : nullptr, shape->kq,
-                               stream);
+                               w.flags, 3 * shape->bh, stream);
     }
     return launch_status();
 }
@@ -1195,7 +1211,7 @@ extern "C" int svoo_assign(const svoo_shape* shape, const void* x, const float* 
     const size_t n_own = (size_t)s.bh * k_own * s.d, n_opp = (size_t)s.bh * k_opp * s.d;
     hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n_own + 255) / 256), dim3(256), 0, stream, c_own, w.c64q, n_own);
     hipLaunchKernelGGL(f32_to_f64_kernel, dim3((n_opp + 255) / 256), dim3(256), 0, stream, c_opp, w.c64k, n_opp);
-    return assign_side(&s, w, x, w.c64q, k_own, w.c64k, k_opp, labels, false, stream);
+    return assign_side(&s, w, x, w.c64q, k_own, w.c64k, k_opp, labels, false, false, stream);
 }
 
 // One Lloyd assignment: labels of x against centroids c64 [bh, k, d].
@@ -1252,7 +1268,7 @@ extern "C" int svoo_kmeans(const svoo_shape* shape, const void* x, int32_t k, co
     const ClusterWs w = carve_cluster_ws(&s, ws);
     if (ws_bytes < w.bytes) return SVOO_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t stream = (hipStream_t)hip_stream;
-    launch_init_centroids(&s, x, init_idx, init_c, w.c64q, k, stream);
+    launch_init_centroids(&s, x, init_idx, init_c, w.c64q, k, nullptr, 0, stream);
     for (int it = 0; it < iters; ++it) {
         const bool last = it == iters - 1;
         st = kmeans_assign(&s, w, x, w.c64q, k, labels, stream);
@@ -1271,7 +1287,7 @@ extern "C" int svoo_kmeans(const svoo_shape* shape, const void* x, int32_t k, co
         st = sort_labels(s.bh, s.n, k, labels, w.perm, w.offsets, nullptr, w.chunk_hist, stream);
         if (st != SVOO_OK) return st;
         launch_centroid_update(&s, x, w.perm, w.offsets, w.c64q, last ? c : nullptr, last ? counts : nullptr, k,
-                               stream);
+                               nullptr, 0, stream);
     }
     return launch_status();
 }

@@ -450,6 +450,7 @@ static void dispatch_token_tile(const svoo_shape* s, const void* x, const double
 // (j, h) holds for token j the centroids 32 cb + 8 (v/4) + 4 h + v%4.
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 #define ASSIGN_LIST_WGS 256   // workgroups per slice that share the queue of undecided tokens
 #define FAST_EPS 3.1e-5f   // 2^-16 + 256 * 2^-24, twice the analytic bound for d <= 128
@@ -703,25 +704,25 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
     };
     issue_block(0, 0);
 
-    // token fragments and squared norms
+    // token fragments and squared norms (the norm only scales the margin below, whose constant has a factor
+    // of two in hand: the packed dot product's own rounding does not matter).  Rows past the end are read
+    // from the last token instead of being predicated; their results are never stored.
     bf16x8_t xf[2][DC];
     float xn2[2];
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
         const int tok = t0 + 32 * tb + j;
-        const bool valid = tok < n;
-        const uint4* src = (const uint4*)(x + ((size_t)b * n + (valid ? tok : 0)) * D);
+        const uint4* src = (const uint4*)(x + ((size_t)b * n + (tok < n ? tok : n - 1)) * D);
         float acc = 0.f;
 #pragma unroll
         for (int c = 0; c < DC; ++c) {
-            const uint4 u = valid ? src[2 * c + h] : make_uint4(0, 0, 0, 0);
+            const uint4 u = src[2 * c + h];
             xf[tb][c] = __builtin_bit_cast(bf16x8_t, u);
             const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float lo = __uint_as_float(wds[e] << 16), hi = __uint_as_float(wds[e] & 0xffff0000u);
-                acc = fmaf(lo, lo, acc);
-                acc = fmaf(hi, hi, acc);
+                const bf16x2_t pr = __builtin_bit_cast(bf16x2_t, wds[e]);
+                acc = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, acc, false);
             }
         }
         const int ai = __float_as_int(acc);

@@ -126,17 +126,22 @@ def workspace_bytes(shape: Shape) -> int:
 _WS: Dict[Tuple[int, int], torch.Tensor] = {}
 
 
-def workspace(shape: Shape, device) -> torch.Tensor:
-    """A cached uint8 device buffer large enough for any call with this shape."""
+def workspace(shape: Shape, device, private: bool = False) -> torch.Tensor:
+    """A uint8 device buffer large enough for any call with this shape.  By default it is ONE cached
+    buffer per device, shared by every call made through this module: calls that may overlap on the GPU
+    (different streams) race on it and must each bring a buffer of their own (``private=True``)."""
     need = workspace_bytes(shape)
     if need == 0:
         raise SvooError(1, "svoo_workspace_bytes")
     dev = torch.device(device)
-    key = (dev.index or 0, 0)
-    buf = _WS.get(key)
-    if buf is None or buf.numel() < need:
+    if private:
         buf = torch.empty(need + 256, dtype=torch.uint8, device=dev)
-        _WS[key] = buf
+    else:
+        key = (dev.index or 0, 0)
+        buf = _WS.get(key)
+        if buf is None or buf.numel() < need:
+            buf = torch.empty(need + 256, dtype=torch.uint8, device=dev)
+            _WS[key] = buf
     off = (-buf.data_ptr()) % 256
     return buf[off:off + need]
 
@@ -435,9 +440,12 @@ def microbench_copy(src, dst):
 
 class Layer:
     """Pre-allocated buffers for the five calls of one layer (what a benchmark or a DiT block keeps
-    alive between diffusion steps).  ``run`` enqueues the whole online stage on the current stream."""
+    alive between diffusion steps).  ``run`` enqueues the whole online stage on the current stream.
+    Layers share the device's cached workspace unless ``own_workspace`` is set: two layers whose calls
+    may overlap on the GPU (different streams) each need their own."""
 
-    def __init__(self, bh: int, n: int, d: int, dtype: torch.dtype, kq: int, kk: int, device="cuda:0"):
+    def __init__(self, bh: int, n: int, d: int, dtype: torch.dtype, kq: int, kk: int, device="cuda:0",
+                 own_workspace: bool = False):
         dev = torch.device(device)
         self.dev = dev
         self.kq, self.kk, self.d = kq, kk, d
@@ -462,7 +470,7 @@ class Layer:
         self.v_sorted = torch.empty((bh, n, d), dtype=dtype, device=dev)
         self.o_sorted = torch.empty((bh, n, d), dtype=dtype, device=dev)
         self.out = torch.empty((bh, n, d), dtype=dtype, device=dev)
-        self.ws = workspace(self.shape, dev)
+        self.ws = workspace(self.shape, dev, private=own_workspace)
 
     # the five calls, individually (the benchmark times them one by one and as a whole)
     def step_cocluster(self, q, k, init_q_idx, init_k_idx, iters):

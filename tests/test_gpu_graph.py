@@ -67,3 +67,40 @@ def test_layer_replays_from_a_graph(partitioner):
         got = snapshot()
         for name in NAMES:
             assert torch.equal(got[name], eager[which][name]), (which, name)
+
+
+def test_two_layers_on_two_streams_with_workspaces_of_their_own():
+    """The binding's cached workspace is one buffer per device; layers whose calls may overlap on the
+    GPU take ``own_workspace=True``.  Two such layers, each on a stream of its own, must give what the
+    same layers give one after the other."""
+    cfg = synth.CONFIGS[1]
+    heads = [[0, 1], [2, 3]]
+    data = [synth.make_layer(cfg, 0, heads=h, workers=4) for h in heads]
+    layers = [svoo.Layer(2, cfg.n, cfg.d, torch.bfloat16, cfg.kq, cfg.kk, H.DEV, own_workspace=True) for _ in heads]
+    assert layers[0].ws.data_ptr() != layers[1].ws.data_ptr()
+    dev = [{k: H.to_dev(d[k], "bf16") for k in "qkv"} for d in data]
+    for t, d in zip(dev, data):
+        t.update({k: H.to_dev(d[k]) for k in ("init_q_idx", "init_k_idx")})
+    keep = H.to_dev(np.full(2, 0.3, dtype=np.float32))
+
+    def step(g):
+        layers[g].run(dev[g]["q"], dev[g]["k"], dev[g]["v"], dev[g]["init_q_idx"], dev[g]["init_k_idx"], cfg.iters,
+                      keep, 0.95, 0.1)
+
+    serial = []
+    for g in range(2):
+        step(g)
+        torch.cuda.synchronize()
+        serial.append({name: getattr(layers[g], name).clone() for name in NAMES})
+    streams = [torch.cuda.Stream() for _ in heads]
+    for rep in range(3):
+        for g in range(2):
+            streams[g].wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(streams[g]):
+                step(g)
+        for g in range(2):
+            torch.cuda.current_stream().wait_stream(streams[g])
+        torch.cuda.synchronize()
+        for g in range(2):
+            for name in NAMES:
+                assert torch.equal(getattr(layers[g], name), serial[g][name]), (rep, g, name)

@@ -277,10 +277,13 @@ int svoo_row_recall(const svoo_shape* shape, const float* lse_kept_sorted, const
  * q, k [bh, n, d]; rows (nullable, then n_rows must equal n) [n_rows] int32; tau in (0, 1] (the
  * paper uses 0.95); prefix_len [bh, n_rows] int32; density [bh] float64; passes (nullable) [bh]
  * int32 = number of passes over the keys the slowest row group of the slice needed (what the
- * call cost: passes x n_rows x n x d multiply-adds).  shape->kq / kk are ignored.  No workspace.  Logits in float32 (bf16 inputs: matrix cores, float32 accumulation),
- * masses added in float32 within 64 keys and in float64 across them; no sort: the cut is found by
- * bisection on the logit value, one pass over the keys per step (about 15-25 passes), so a call
- * costs that many score-matrix computations for the listed rows.
+ * call cost: passes x n_rows x n x d multiply-adds).  shape->kq / kk are ignored.  No workspace.
+ * Logits in float32 (bf16 inputs: matrix cores, float32 accumulation), masses added in float32
+ * within 64 keys and in float64 across them, in a fixed order that depends only on the shape of
+ * the call (small row samples split the keys between the waves of a workgroup), so a result is
+ * reproducible and two shapes can differ only where a cumulative sum meets tau to rounding.  No
+ * sort: the cut is found by bisection on the logit value, one pass over the keys per step (about
+ * 30 passes at 75,600 keys), so a call costs that many score-matrix computations for the listed rows.
  */
 int svoo_attention_density(const svoo_shape* shape, const void* q, const void* k, const int32_t* rows,
                            int32_t n_rows, float tau, float scale, int32_t* prefix_len, double* density,

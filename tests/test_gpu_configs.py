@@ -151,6 +151,17 @@ def test_paper_hyperparameters_asymmetric_clusters():
     print(f"paper hyper-parameters: {stats}")
 
 
+def test_paper_hyperparameters_long_sequence():
+    """The same settings (K_q = 256, K_k = 1024, two iterations) on the long grid, N = 118,800, with its
+    skewed region sizes: key blocks of ~116 rows on average and far smaller ones in the tail of the
+    size distribution."""
+    cfg = dataclasses.replace(synth.CONFIGS[4], name="paper hyper-parameters, long sequence", kq=256, kk=1024, iters=2)
+    data, dev, layer, out, stats = run_and_check(cfg, [3, 20], 0.2, 0.95, 0.1, n_rows=1024, oracle_label_heads=(),
+                                                 check_assign=False)
+    counts = H.to_np(layer.counts_k)
+    print(f"paper hyper-parameters at N = {cfg.n}: {stats}; key cluster sizes min {counts.min()} max {counts.max()}")
+
+
 def test_maximum_cluster_counts_both_sides():
     """K_q = K_k = 1024 (the largest the library takes) on the 480p grid: query blocks of ~32 rows, so
     nearly every attention tile is a short one whose waves divide the keys, and every mask row ranks

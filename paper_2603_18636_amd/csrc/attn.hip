@@ -125,9 +125,14 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
     const int32_t* qo = a.q_offsets + (size_t)b * (a.kq + 1);
     const int t = slot - tp[r];
     ti.r = r;
-    ti.q0 = qo[r] + t * bm;
-    const int rem = qo[r + 1] - ti.q0;
-    ti.qn = rem < bm ? rem : bm;
+    // offsets come from the caller: whatever they hold, rows stay inside [0, n)
+    int q0 = qo[r] + t * bm;
+    q0 = q0 < 0 ? 0 : (q0 >= a.n ? a.n - 1 : q0);
+    int q1 = qo[r + 1];
+    q1 = q1 > a.n ? a.n : q1;
+    ti.q0 = q0;
+    const int rem = q1 - q0;
+    ti.qn = rem < bm ? (rem < 0 ? 0 : rem) : bm;
     int cnt = a.block_count[(size_t)b * a.kq + r];
     cnt = cnt < 0 ? 0 : (cnt > a.kk ? a.kk : cnt);
     const int32_t* bl = a.block_list + ((size_t)b * a.kq + r) * a.kk;
@@ -141,9 +146,11 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
         if (i < cnt) {
             int j = bl[i];
             j = j < 0 ? 0 : (j >= a.kk ? a.kk - 1 : j);
-            start[u] = ko[j];
-            len[u] = ko[j + 1] - ko[j];
-            len[u] = len[u] < 0 ? 0 : len[u];
+            int s0 = ko[j], s1 = ko[j + 1];
+            s0 = s0 < 0 ? 0 : (s0 > a.n ? a.n : s0);
+            s1 = s1 > a.n ? a.n : s1;
+            start[u] = s0;
+            len[u] = s1 > s0 ? s1 - s0 : 0;
         }
         local += len[u];
     }

@@ -325,6 +325,7 @@ token_tile_kernel(const T* __restrict__ x, const double* __restrict__ bmat, int 
 // order, hence the same bits, as token_tile_kernel<MODE_ARGMAX>.  No cross-lane sums; one
 // (value, index) reduction per token at the end.
 // ---------------------------------------------------------------------------------------------
+#define LIST_BATCH 32   // loads of W^T in flight per thread
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
 assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wt, int k_own,
@@ -336,11 +337,13 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wt, int k
     __shared__ double best_v[4];
     __shared__ int32_t best_j[4];
     const int b = blockIdx.y, tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
-    const int count = list_count[b];
+    int count = list_count[b];
+    count = count > n ? n : count;
     const bool general = force_general || flags[b] != 0;
     const double* wb = wt + (size_t)b * D * k_own;
     for (int p = blockIdx.x; p < count; p += gridDim.x) {
-        const int ti = list[(size_t)b * n + p];
+        int ti = list[(size_t)b * n + p];
+        ti = ti < 0 ? 0 : (ti >= n ? n - 1 : ti);
         if (tid < D) xs[tid] = load_as_f64<T>(x + ((size_t)b * n + ti) * D + tid);
         double nx = 0.0;
         if (general) {
@@ -354,8 +357,18 @@ assign_list_kernel(const T* __restrict__ x, const double* __restrict__ wt, int k
         for (int j = tid; j < k_own; j += 256) {         // ascending j per thread: ">" keeps the lowest index
             const double* wc = wb + j;
             double sum = 0.0;
-#pragma unroll 16
-            for (int c = 0; c < D; ++c) sum = fma(xs[c], wc[(size_t)c * k_own], sum);
+            // LIST_BATCH loads in flight, then their products: the fence keeps the compiler from turning the
+            // batch into one load and one wait at a time (the loads are long round trips)
+#pragma unroll 1
+            for (int c0 = 0; c0 < D; c0 += LIST_BATCH) {
+                double wv[LIST_BATCH];
+#pragma unroll
+                for (int u = 0; u < LIST_BATCH; ++u) wv[u] = wc[(size_t)(c0 + u) * k_own];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < LIST_BATCH; ++u) sum = fma(xs[c0 + u], wv[u], sum);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             const double val = general ? 2.0 * sum - nx * bterm[(size_t)b * k_own + j] : sum;
             if (val > best || bj == 0x7fffffff) {
                 best = val;
@@ -828,7 +841,7 @@ assign_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ 
             labels[(size_t)b * n + tok] = fi;
             if (degenerate || !sure) {
                 const int pos = atomicAdd(&list_count[b], 1);
-                list[(size_t)b * n + pos] = tok;
+                if (pos >= 0 && pos < n) list[(size_t)b * n + pos] = tok;   // always true when the counter started at zero
             }
         }
     }
@@ -871,8 +884,14 @@ centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm
     __shared__ double part[GROUPS][D];
     const int b = blockIdx.y, j = blockIdx.x;
     const int lane = threadIdx.x % LANES, grp = threadIdx.x / LANES;
-    const int beg = offsets[(size_t)b * (k + 1) + j], end = offsets[(size_t)b * (k + 1) + j + 1];
+    int beg = offsets[(size_t)b * (k + 1) + j], end = offsets[(size_t)b * (k + 1) + j + 1];
+    beg = beg < 0 ? 0 : beg;
+    end = end > n ? n : end;
     const int32_t* pm = perm + (size_t)b * n;
+    auto member = [&](int pos) {       // a permutation entry outside [0, n) must not leave the tensor
+        const int t = pm[pos];
+        return t < 0 ? 0 : (t >= n ? n - 1 : t);
+    };
     const T* xb = x + (size_t)b * n * D + 8 * lane;
     double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int p = beg + grp;
@@ -883,7 +902,7 @@ centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm
         for (; p + (ROWS - 1) * GROUPS < end; p += ROWS * GROUPS) {
             double a[ROWS][8];
 #pragma unroll
-            for (int r = 0; r < ROWS; ++r) load8_as_f64<T>(xb + (size_t)pm[p + r * GROUPS] * D, a[r]);
+            for (int r = 0; r < ROWS; ++r) load8_as_f64<T>(xb + (size_t)member(p + r * GROUPS) * D, a[r]);
 #pragma unroll
             for (int r = 0; r < ROWS; ++r)
 #pragma unroll
@@ -894,7 +913,7 @@ centroid_update_kernel(const T* __restrict__ x, const int32_t* __restrict__ perm
     batch(std::integral_constant<int, 2>{});
     if (p < end) {
         double a0[8];
-        load8_as_f64<T>(xb + (size_t)pm[p] * D, a0);
+        load8_as_f64<T>(xb + (size_t)member(p) * D, a0);
 #pragma unroll
         for (int e = 0; e < 8; ++e) s[e] += a0[e];
     }

@@ -145,7 +145,8 @@ sort_scatter_kernel(const int32_t* __restrict__ labels, const int32_t* __restric
         int first = 0;
         if (valid) {
             first = cnt[label];
-            out[first + __popcll(same & lt_mask)] = i;
+            const int pos = first + __popcll(same & lt_mask);
+            if (pos >= 0 && pos < n) out[pos] = i;     // always true for the histogram of these labels
         }
         __builtin_amdgcn_wave_barrier();
         if (valid && (same & lt_mask) == 0) cnt[label] = first + __popcll(same);   // lowest lane of each label
@@ -183,7 +184,8 @@ move_rows_kernel(RowPtrs ptrs, const int32_t* __restrict__ perm, int n, int vec_
     const int v = threadIdx.x % vec_per_row;
     const int p = blockIdx.x * rows_per_block + row_in_block;
     if (row_in_block >= rows_per_block || p >= n) return;
-    const int token = perm[(size_t)b * n + p];
+    int token = perm[(size_t)b * n + p];
+    token = token < 0 ? 0 : (token >= n ? n - 1 : token);   // an entry outside [0, n) must not leave the tensor
     const uint4* src = ptrs.src[t] + (size_t)b * n * vec_per_row;
     uint4* dst = ptrs.dst[t] + (size_t)b * n * vec_per_row;
     if (GATHER)

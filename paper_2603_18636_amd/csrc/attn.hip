@@ -154,15 +154,21 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
         }
         local += len[u];
     }
+    // Prefix sums that saturate at n: distinct key blocks never hold more than n keys, so nothing changes
+    // for a valid block list; a list with repeated or overlapping blocks cannot overflow the sums or make
+    // them decrease, which is what the walk along the stream relies on to end.
+    const int cap = a.n;
+    local = local < cap ? local : cap;
     scan[tid] = local;
     __syncthreads();
     for (int s = 1; s < NT; s <<= 1) {
         const int v = tid >= s ? scan[tid - s] : 0;
         __syncthreads();
-        scan[tid] += v;
+        const int t = scan[tid] + v;
+        scan[tid] = t < cap ? t : cap;
         __syncthreads();
     }
-    int run = scan[tid] - local;
+    int run = tid > 0 ? scan[tid - 1] : 0;
 #pragma unroll
     for (int u = 0; u < SPT; ++u) {
         const int i = tid * SPT + u;
@@ -171,6 +177,7 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
             seg_cum[i] = run;
         }
         run += len[u];
+        run = run < cap ? run : cap;
     }
     ti.total = scan[NT - 1];
     ti.n_seg = cnt;

@@ -56,6 +56,27 @@ def test_permute_unpermute_rows(dtype, d):
     assert (H.to_np(back) == xs[1]).all()
 
 
+def test_row_movers_clamp_entries_outside_the_tensor():
+    """A permutation entry outside [0, n) breaks the contract; the row movers read (or write) the nearest
+    valid row instead of leaving the tensor."""
+    rng = np.random.default_rng(11)
+    bh, n, d = 2, 777, 64
+    x = synth.round_to_bf16(rng.standard_normal((bh, n, d)).astype(np.float32))
+    perm = np.stack([rng.permutation(n) for _ in range(bh)]).astype(np.int32)
+    bad = perm.copy()
+    bad[0, 5], bad[0, 100], bad[1, 0], bad[1, n - 1] = -7, n + 5, 2 ** 30, -(2 ** 31)
+    got = H.to_np(svoo.gather(H.to_dev(bad), [H.to_dev(x, "bf16")])[0])
+    want = np.stack([x[b][np.clip(bad[b].astype(np.int64), 0, n - 1)] for b in range(bh)])
+    assert (got == want).all()
+    # scatter: rows whose entry was in range land where they should (the clamped ones collide with them)
+    back = H.to_np(svoo.unpermute(H.to_dev(x, "bf16"), H.to_dev(bad)))
+    for b in range(bh):
+        ok = (bad[b] >= 0) & (bad[b] < n)
+        clamped = np.clip(bad[b][~ok].astype(np.int64), 0, n - 1)
+        keep = ok & ~np.isin(bad[b], clamped)
+        assert (back[b][bad[b][keep]] == x[b][keep]).all()
+
+
 # ------------------------------------------------------------------------------------------ assign
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
 def test_assign_matches_oracle_teacher_forced(dtype, d):

@@ -37,6 +37,10 @@
  *    svoo_cocluster, and is never selected by svoo_block_mask.
  *  - Outputs are fully overwritten.  Results are deterministic: the same inputs give the same
  *    bits on every run (no floating-point atomics anywhere).
+ *  - Index arrays (labels, anchor indices, permutations, offsets, block counts and lists, row lists)
+ *    live in device memory, so the host cannot validate them.  An entry outside its range is clamped
+ *    into it before it addresses anything: the result of such a call is meaningless, but no memory
+ *    outside the tensors of the call is read or written and every kernel ends.
  */
 #ifndef SVOO_H
 #define SVOO_H

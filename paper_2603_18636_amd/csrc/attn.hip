@@ -34,12 +34,16 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // schedule: tile_prefix[b, r] = number of query tiles of blocks < r  (kq + 1 entries per slice)
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(1024)
-attn_schedule_kernel(const int32_t* __restrict__ q_offsets, int32_t* __restrict__ tile_prefix, int kq, int bm) {
+attn_schedule_kernel(const int32_t* __restrict__ q_offsets, int32_t* __restrict__ tile_prefix, int kq, int bm,
+                     int n) {
     __shared__ int32_t scan[1024];
     const int b = blockIdx.x, r = threadIdx.x;
     int tiles = 0;
     if (r < kq) {
-        const int len = q_offsets[(size_t)b * (kq + 1) + r + 1] - q_offsets[(size_t)b * (kq + 1) + r];
+        int lo = q_offsets[(size_t)b * (kq + 1) + r], hi = q_offsets[(size_t)b * (kq + 1) + r + 1];
+        lo = lo < 0 ? 0 : (lo > n ? n : lo);          // the same clamps as where the tile is set up
+        hi = hi < 0 ? 0 : (hi > n ? n : hi);
+        const int len = hi - lo;
         tiles = len > 0 ? (len + bm - 1) / bm : 0;
     }
     scan[r] = tiles;
@@ -126,10 +130,10 @@ __device__ __forceinline__ bool setup_tile(const AttnArgs& a, int bm, int32_t* s
     const int t = slot - tp[r];
     ti.r = r;
     // offsets come from the caller: whatever they hold, rows stay inside [0, n)
-    int q0 = qo[r] + t * bm;
-    q0 = q0 < 0 ? 0 : (q0 >= a.n ? a.n - 1 : q0);
+    const long long q0l = (long long)qo[r] + (long long)t * bm;
+    const int q0 = q0l < 0 ? 0 : (q0l >= a.n ? a.n - 1 : (int)q0l);
     int q1 = qo[r + 1];
-    q1 = q1 > a.n ? a.n : q1;
+    q1 = q1 < 0 ? 0 : (q1 > a.n ? a.n : q1);
     ti.q0 = q0;
     const int rem = q1 - q0;
     ti.qn = rem < bm ? (rem < 0 ? 0 : rem) : bm;
@@ -793,7 +797,8 @@ static int launch_bf16(dim3 grid, const AttnArgs& a, hipStream_t stream) {
 // dense = one-block layout: every workgroup reads the same key stream
 static int launch_sparse(const svoo_shape* s, AttnArgs& a, int32_t* tile_prefix, bool dense, hipStream_t stream) {
     const int bm = s->dtype == SVOO_BF16 ? 32 * (dense ? DENSE_NW : SVOO_SPARSE_NW) : BM_F32;
-    hipLaunchKernelGGL(attn_schedule_kernel, dim3(s->bh), dim3(1024), 0, stream, a.q_offsets, tile_prefix, a.kq, bm);
+    hipLaunchKernelGGL(attn_schedule_kernel, dim3(s->bh), dim3(1024), 0, stream, a.q_offsets, tile_prefix, a.kq, bm,
+                       s->n);
     a.tile_prefix = tile_prefix;
     int gx = (s->n + bm - 1) / bm + a.kq;
     gx = (gx + 7) / 8 * 8;

@@ -360,6 +360,42 @@ def test_sparse_attn_short_query_blocks_and_short_key_streams(d):
     np.testing.assert_allclose(lse, lse_ref, atol=2e-2)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_sparse_attn_with_index_arrays_that_break_the_contract(dtype):
+    """Offsets, block counts and block lists full of arbitrary integers (negative, far beyond n, not
+    monotone, repeated blocks): the call must end without touching memory outside its tensors -- the
+    result is meaningless -- and a valid call right after it must be correct."""
+    rng = np.random.default_rng(23)
+    bh, n, d, kq, kk = 2, 700, 128, 9, 13
+    x = [synth.round_to_bf16(rng.standard_normal((bh, n, d)).astype(np.float32)) for _ in range(3)]
+    q, k, v = (H.to_dev(t, dtype) for t in x)
+    scale = H.scale_of(d)
+    wide = lambda shape: rng.choice(np.array([-2 ** 31, -5, -1, 0, 1, 3, n // 2, n - 1, n, n + 1, 5 * n, 2 ** 31 - 1]),
+                                    size=shape).astype(np.int32)
+    for trial in range(4):
+        out = svoo.block_sparse_attn(q, k, v, H.to_dev(wide((bh, kq + 1))), H.to_dev(wide((bh, kk + 1))),
+                                     H.to_dev(wide((bh, kq))), H.to_dev(wide((bh, kq, kk))), scale)
+        torch.cuda.synchronize()
+        assert out.shape == (bh, n, d)
+    # valid layout right after
+    labels_q = rng.integers(0, kq, size=(bh, n)).astype(np.int32)
+    labels_k = rng.integers(0, kk, size=(bh, n)).astype(np.int32)
+    mask = rng.random((bh, kq, kk)) < 0.4
+    perm_q, q_off, (qs,) = svoo.permute(H.to_dev(labels_q), kq, [q])
+    perm_k, k_off, (ks, vs) = svoo.permute(H.to_dev(labels_k), kk, [k, v])
+    count = mask.sum(2).astype(np.int32)
+    blist = np.full((bh, kq, kk), -1, dtype=np.int32)
+    for b in range(bh):
+        for r in range(kq):
+            ids = np.nonzero(mask[b, r])[0]
+            blist[b, r, :ids.size] = ids
+    out = svoo.unpermute(svoo.block_sparse_attn(qs, ks, vs, q_off, k_off, H.to_dev(count), H.to_dev(blist), scale), perm_q)
+    out = H.to_np(out)
+    for b in range(bh):
+        ref = so.sparse_attention(x[0][b], x[1][b], x[2][b], labels_q[b], labels_k[b], mask[b], scale)
+        H.assert_attn_close(out[b], ref, dtype, f"valid call after the broken ones, slice {b}")
+
+
 def test_sparse_attn_no_kept_block_writes_zeros():
     h = small_cfg1_head(dtype="bf16")
     n = h["q"].shape[0]
